@@ -1,0 +1,255 @@
+"""Pins for the oracle's convolution routines (CPU only).
+
+direct fp64      vs the exact rational definition (tiny) and a library fp64 convolution
+Winograd exact   == direct, in rational arithmetic, on tiny integer inputs (ragged too)
+Winograd fp64    vs direct fp64, all tile sizes / point sets, ragged shapes
+fp16 rounding    vs numpy's double -> half conversion
+emulation        exact special cases where no rounding can occur; error ordering;
+                 binary16 overflow of the integer-point F(8,3) transform
+"""
+import random
+from fractions import Fraction as Fr
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import conv, cook_toom as ct, exact
+from paper_2512_18453_amd import synth
+
+
+def pts(pairs):
+    return [Fr(a, b) for a, b in pairs]
+
+
+def rel_l2(a, b):
+    return float(np.linalg.norm((a - b).ravel()) / np.linalg.norm(b.ravel()))
+
+
+def int_case(rnd, N, C, K, H, W, lim=3):
+    x = [[[[rnd.randint(-lim, lim) for _ in range(W)] for _ in range(H)] for _ in range(C)] for _ in range(N)]
+    g = [[[[rnd.randint(-lim, lim) for _ in range(3)] for _ in range(3)] for _ in range(C)] for _ in range(K)]
+    return x, g
+
+
+# ---------------------------------------------------------------- exact arithmetic
+
+
+@pytest.mark.parametrize("m,name", [(2, "standard"), (4, "standard"), (4, "nova"), (6, "nova"), (8, "nova")])
+def test_winograd_equals_direct_in_rational_arithmetic(m, name):
+    rnd = random.Random(100 + m)
+    A, BT, G = ct.cook_toom(pts(synth.point_set(name, m)), m, 3)
+    # one whole tile, and a ragged shape that needs a partial last tile row and column
+    for (H, W) in [(m, m), (m + 3, 2 * m - 1)]:
+        x, g = int_case(rnd, 1, 2, 2, H, W)
+        assert exact.winograd_conv2d(x, g, A, BT, G) == exact.direct_conv2d(x, g)
+
+
+def test_direct_c_equals_exact_definition_on_integers():
+    rnd = random.Random(5)
+    x, g = int_case(rnd, 2, 3, 2, 5, 7, lim=9)
+    want = np.array([[[[float(v) for v in row] for row in pl] for pl in img]
+                     for img in exact.direct_conv2d(x, g)])
+    got = conv.direct_conv2d(np.array(x, dtype=np.float64), np.array(g, dtype=np.float64))
+    assert np.array_equal(got, want)        # small integers: fp64 is exact
+
+
+def test_direct_by_hand_single_pixel():
+    # a single 1 at (1,2) in a 4x4 image: y[h][w] = g[1-h+1][2-w+1] (correlation, no flip)
+    x = np.zeros((1, 1, 4, 4)); x[0, 0, 1, 2] = 1.0
+    g = np.arange(1.0, 10.0).reshape(1, 1, 3, 3)
+    y = conv.direct_conv2d(x, g)
+    want = np.zeros((4, 4))
+    for h in range(4):
+        for w in range(4):
+            a, b = 1 - h + 1, 2 - w + 1
+            if 0 <= a < 3 and 0 <= b < 3:
+                want[h, w] = g[0, 0, a, b]
+    assert np.array_equal(y[0, 0], want)
+    assert y[0, 0, 0, 1] == 9.0 and y[0, 0, 2, 3] == 1.0
+
+
+# ---------------------------------------------------------------- fp64
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 4, 9, 13), (1, 16, 16, 32, 32), (3, 5, 2, 1, 1), (1, 1, 1, 2, 17)])
+def test_direct_c_vs_library_conv(shape):
+    N, C, K, H, W = shape
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((N, C, H, W))
+    g = rng.standard_normal((K, C, 3, 3))
+    want = torch.nn.functional.conv2d(torch.from_numpy(x), torch.from_numpy(g), padding=1).numpy()
+    got = conv.direct_conv2d(x, g)
+    assert np.allclose(got, want, rtol=0, atol=1e-12 * np.abs(want).max() * C)
+
+
+CASES_F64 = [(2, "standard", 1e-14), (4, "standard", 1e-13), (4, "nova", 1e-13), (6, "standard", 1e-11),
+             (6, "nova", 1e-12), (6, "classic_half", 1e-12), (8, "nova", 1e-11), (8, "standard", 1e-8)]
+
+
+@pytest.mark.parametrize("m,name,tol", CASES_F64)
+def test_winograd_f64_vs_direct(m, name, tol):
+    rng = np.random.default_rng(20 + m)
+    for (N, C, K, H, W) in [(2, 5, 3, 2 * m, 3 * m), (1, 4, 6, 2 * m + 3, m + 1), (1, 2, 2, 3, 5)]:
+        x = rng.standard_normal((N, C, H, W))
+        g = rng.standard_normal((K, C, 3, 3))
+        want = conv.direct_conv2d(x, g)
+        got = conv.winograd_conv2d_f64(x, g, pts(synth.point_set(name, m)), m)
+        assert rel_l2(got, want) < tol
+
+
+def test_winograd_f64_is_exact_on_small_integers():
+    # integer points, integer data scaled so that G g G^T is integral: nothing rounds in fp64
+    rng = np.random.default_rng(3)
+    x = rng.integers(-4, 5, size=(1, 3, 9, 10)).astype(np.float64)
+    g = 576.0 * rng.integers(-3, 4, size=(2, 3, 3, 3)).astype(np.float64)    # 576 = 24^2
+    want = conv.direct_conv2d(x, g)
+    got = conv.winograd_conv2d_f64(x, g, pts(synth.STANDARD[4]), 4)
+    assert np.array_equal(got, want)
+
+
+# ---------------------------------------------------------------- binary16 rounding
+
+
+def test_round_f16_matches_numpy_conversion():
+    rng = np.random.default_rng(0)
+    vals = np.concatenate([
+        rng.standard_normal(20000) * np.exp(rng.uniform(-18, 12, 20000)),
+        rng.uniform(-2 ** -13, 2 ** -13, 5000),                    # sub-normal range
+        np.array([0.0, -0.0, 65504.0, 65519.999, 65520.0, 65535.0, 65536.0, 1e9, -1e9, np.inf, -np.inf,
+                  2 ** -24, 2 ** -25, 2 ** -25 * 1.0000001, 3 * 2 ** -25, 2 ** -14, 2 ** -14 - 2 ** -26,
+                  1.0 + 2 ** -11, 1.0 + 3 * 2 ** -11, 1.0 + 2 ** -11 + 2 ** -30, 2047.5, 2048.5, 4097.0]),
+    ])
+    # exact ties at every binade
+    halves = np.arange(1024, 2048, dtype=np.float64)
+    ties = np.concatenate([(halves + 0.5) * 2.0 ** e for e in range(-24, 6)])
+    vals = np.concatenate([vals, ties, -ties])
+    with np.errstate(over="ignore"):
+        want = vals.astype(np.float16).astype(np.float64)
+    got = conv.round_f16(vals)
+    assert np.array_equal(got, want)
+    assert np.array_equal(np.signbit(got), np.signbit(want))
+    assert np.isnan(conv.round_f16(np.array([np.nan]))[0])
+
+
+# ---------------------------------------------------------------- emulation
+
+
+def test_emulated_f23_integer_points_is_exact_on_small_integers():
+    # F(2,3), points {0, 1, -1}: G has entries 0, +-1/2, 1, so with even-integer filters every
+    # intermediate is a small integer, exactly representable in binary16 -> no rounding anywhere.
+    rng = np.random.default_rng(8)
+    x = rng.integers(-3, 4, size=(2, 3, 7, 6)).astype(np.float64)
+    g = 4.0 * rng.integers(-2, 3, size=(4, 3, 3, 3)).astype(np.float64)
+    want = conv.direct_conv2d(x, g)
+    assert np.abs(want).max() < 2048
+    for m_storage in (16, 32):
+        got = conv.winograd_conv2d_emulated(x, g, pts(synth.STANDARD[2]), 2, storage=16, m_storage=m_storage)
+        assert np.array_equal(got, want)
+
+
+def test_emulated_f43_integer_points_is_exact_on_scaled_integers():
+    # F(4,3), integer points: weights that are multiples of 576 = 24^2 make U integral; tiny x keeps
+    # V (|B^T| row sums <= 10, squared) and U below 2048 in magnitude, M and y below 65504.
+    rng = np.random.default_rng(9)
+    x = rng.integers(-1, 2, size=(1, 2, 8, 9)).astype(np.float64)
+    g = 576.0 * rng.integers(-1, 2, size=(2, 2, 3, 3)).astype(np.float64)
+    want = conv.direct_conv2d(x, g)
+    y, U, V, M = conv.winograd_conv2d_emulated(x, g, pts(synth.STANDARD[4]), 4, storage=16,
+                                               want_intermediates=True)
+    assert np.abs(U).max() <= 2048 and np.abs(V).max() <= 2048
+    assert np.array_equal(U, np.round(U)) and np.array_equal(V, np.round(V))
+    exact_ok = np.abs(want) <= 2048              # integers up to 2048 are exact in binary16
+    assert exact_ok.mean() > 0.5
+    assert np.array_equal(y[exact_ok], want[exact_ok])
+    assert np.allclose(y, want, rtol=2.0 ** -11, atol=0)      # the rest: one rounding of an exact value
+
+
+def test_emulated_intermediates_have_the_documented_layout():
+    # V of a single 1 at input position (a,b) of the only tile is the outer product of columns a and
+    # b of B^T (all exact for integer points); U of a one-hot filter is the outer product of G columns.
+    m, n = 4, 6
+    A, BT, G = ct.cook_toom(pts(synth.STANDARD[m]), m, 3)
+    x = np.zeros((1, 2, 4, 4)); x[0, 1, 1, 2] = 1.0          # tile position a = 2, b = 3 (pad 1)
+    g = np.zeros((3, 2, 3, 3)); g[2, 1, 0, 2] = 24.0
+    _, U, V, M = conv.winograd_conv2d_emulated(x, g, pts(synth.STANDARD[m]), m, storage=32,
+                                               want_intermediates=True)
+    assert U.shape == (n * n, 3, 2) and V.shape == (n * n, 1, 2) and M.shape == (n * n, 1, 3)
+    BTf, Gf = ct.to_f64(BT), ct.to_f64(G)
+    assert np.array_equal(V[:, 0, 1].reshape(n, n), np.outer(BTf[:, 2], BTf[:, 3]))
+    assert not V[:, 0, 0].any()
+    wantU = np.float32(24.0 * np.outer(Gf[:, 0], Gf[:, 2])).astype(np.float64)
+    assert np.array_equal(U[:, 2, 1].reshape(n, n), wantU)
+    assert np.array_equal(M[:, 0, 2], np.float32(U[:, 2, 1] * V[:, 0, 1]).astype(np.float64))
+
+
+def test_emulated_f32_chain_is_within_fp32_rounding_of_exact_transform():
+    # |V_fp32chain - B^T d B| <= 2 n eps32 * (|B^T| |d| |B|): the standard bound for two nested
+    # length-n dot products, entry by entry
+    m, n = 8, 10
+    points = pts(synth.NOVA[m])
+    rng = np.random.default_rng(13)
+    x = np.abs(rng.standard_normal((1, 3, 16, 16))).astype(np.float16).astype(np.float64)
+    g = rng.standard_normal((1, 3, 3, 3)).astype(np.float16).astype(np.float64)
+    _, _, V32, _ = conv.winograd_conv2d_emulated(x, g, points, m, storage=32, want_intermediates=True)
+    BT = ct.to_f32(ct.cook_toom(points, m, 3)[1]).astype(np.float64)
+    xp = np.zeros((3, 18, 18)); xp[:, 1:17, 1:17] = x[0]
+    t = 0
+    for tr in range(2):
+        for tc in range(2):
+            for c in range(3):
+                d = xp[c, tr * 8:tr * 8 + 10, tc * 8:tc * 8 + 10]
+                want = BT @ d @ BT.T
+                bound = 2 * n * 2.0 ** -24 * (np.abs(BT) @ np.abs(d) @ np.abs(BT.T)) + 1e-30
+                got = V32[:, t, c].reshape(n, n)
+                assert (np.abs(got - want) <= bound).all()
+                assert np.abs(got - want).max() > 0          # it is a binary32 computation, not fp64
+            t += 1
+
+
+@pytest.mark.parametrize("m,name,lo,hi", [(4, "standard", 2e-4, 6e-3), (4, "nova", 2e-4, 6e-3),
+                                          (6, "classic_half", 5e-4, 2e-2), (6, "nova", 3e-3, 1e-1),
+                                          (8, "nova", 5e-2, 1.0)])
+def test_emulated_fp16_error_magnitude_and_ordering(m, name, lo, hi):
+    points = pts(synth.point_set(name, m))
+    x, g = synth.make_layer(2, 32, 8, 2 * m + 3, 3 * m, seed=77, dtype="f16")
+    x64, g64 = x.astype(np.float64), g.astype(np.float64)
+    want = conv.direct_conv2d(x64, g64)
+    e64 = rel_l2(conv.winograd_conv2d_f64(x64, g64, points, m), want)
+    e16 = rel_l2(conv.winograd_conv2d_emulated(x64, g64, points, m, storage=16), want)
+    e16m = rel_l2(conv.winograd_conv2d_emulated(x64, g64, points, m, storage=16, m_storage=16), want)
+    e16x = rel_l2(conv.winograd_conv2d_emulated(x64, g64, points, m, storage=16, v_exact=True), want)
+    e32 = rel_l2(conv.winograd_conv2d_emulated(x64, g64, points, m, storage=32), want)
+    assert e64 < 1e-10 < e32 < e16             # coarser storage, larger error
+    assert lo < e16 < hi, e16
+    assert e16m > 0.7 * e16                    # rounding M as well does not help
+    assert 0.5 * e16 < e16x < 2.0 * e16        # one vs two roundings of V: same order of magnitude
+
+
+def test_integer_point_f83_overflows_binary16():
+    # Sec. "INT8 ..."/fp16 remark: standard F(6,3)/F(8,3) intermediates can exceed 65504 -> inf/NaN
+    x, g = synth.make_layer(1, 16, 4, 16, 16, seed=5, dtype="f16")
+    x64, g64 = x.astype(np.float64), g.astype(np.float64)
+    y, U, V, M = conv.winograd_conv2d_emulated(x64, g64, pts(synth.STANDARD[8]), 8, storage=16,
+                                               want_intermediates=True)
+    assert np.isinf(V).mean() > 0.2
+    assert (~np.isfinite(y)).mean() > 0.9
+    y_nova = conv.winograd_conv2d_emulated(x64, g64, pts(synth.NOVA[8]), 8, storage=16)
+    assert np.isfinite(y_nova).all()
+
+
+def test_emulated_relu_and_transform_dtype_option():
+    points = pts(synth.NOVA[4])
+    x, g = synth.make_layer(1, 8, 4, 9, 9, seed=6, dtype="f16", x_dist="normal")
+    x64, g64 = x.astype(np.float64), g.astype(np.float64)
+    y = conv.winograd_conv2d_emulated(x64, g64, points, 4, storage=16)
+    yr = conv.winograd_conv2d_emulated(x64, g64, points, 4, storage=16, relu=True)
+    assert np.array_equal(yr, np.maximum(y, 0.0))
+    y16 = conv.winograd_conv2d_emulated(x64, g64, points, 4, storage=16, transform_dtype="f16")
+    want = conv.direct_conv2d(x64, g64)
+    assert rel_l2(y16, want) < 2e-2 and not np.array_equal(y16, y)
+
+
+def test_relu_maxpool():
+    y = np.array([[[[1.0, -2.0, 3.0, 0.5], [-1.0, -3.0, 2.0, 7.0]]]])
+    assert np.array_equal(conv.relu_maxpool2x2(y), np.array([[[[1.0, 7.0]]]]))
