@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the Winograd F(8 x 8, 3 x 3) hot path on one MI355X.
+
+A step is one nova_winograd_conv2d call (input transform -> 100 channel contractions -> output
+transform) on the VGG-16 conv3 shape (N=32, C=K=256, 56x56, fp16 storage, fp32 accumulation,
+NOVA points), inputs resident in HBM; the filter transform is done once outside the timed region.
+Prints ONE JSON line: effective TFLOP/s counted in direct-convolution FLOPs, the roofline figure
+of the dominant kernel, per-stage figures, the fp16 error against the fp64 definition, and the
+CPU oracle's direct convolution timed on the host cores on a bounded sample of the same tensors.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+from fractions import Fraction
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="vgg_conv3_f83_fp16")
+    ap.add_argument("--points", default="nova")
+    ap.add_argument("--images-per-slab", type=int, default=0, help="0 = library default")
+    ap.add_argument("--m-f16", action="store_true", help="keep the products M in fp16 (NOVA_FLAG_M_F16)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path shards by batch with no exchange; "
+                 "see DESIGN.md) -- use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    from paper_2512_18453_amd import nova, synth
+
+    cfg = synth.LAYER_CONFIGS[args.workload]
+    N, C, K, H, W, m = cfg["N"], cfg["C"], cfg["K"], cfg["H"], cfg["W"], cfg["m"]
+    n = m + 2
+    tdtype = torch.float16 if cfg["dtype"] == "f16" else torch.float32
+    dt = nova.NOVA_F16 if cfg["dtype"] == "f16" else nova.NOVA_F32
+    es = 2 if cfg["dtype"] == "f16" else 4
+    flags = nova.NOVA_FLAG_M_F16 if args.m_f16 else 0
+    m_es = 2 if (args.m_f16 and dt == nova.NOVA_F16) else 4
+    points = synth.point_set(args.points, m)
+
+    x, w = synth.make_layer(N, C, K, H, W, seed=cfg["seed"], dtype=cfg["dtype"], x_dist=cfg["x_dist"])
+    dev = "cuda:0"
+    xd, wd = torch.from_numpy(x).to(dev), torch.from_numpy(w).to(dev)
+    t = nova.nova_make_transforms(points, m, 3)
+    U = nova.nova_filter_transform(t, wd)
+    ws_bytes = nova.nova_conv2d_workspace_bytes(N, C, H, W, K, m, dt, flags, args.images_per_slab)
+    one_bytes = nova.nova_conv2d_workspace_bytes(N, C, H, W, K, m, dt, flags, 1)
+    slab_imgs = min(N, max(1, ws_bytes // one_bytes))
+    n_slabs = -(-N // slab_imgs)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    y = torch.empty((N, K, H, W), dtype=tdtype, device=dev)
+
+    def step():
+        nova.nova_winograd_conv2d(t, xd, U, K, y=y, flags=flags, workspace=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    ms_per_step = max(ms_per_step, wall_ms) if wall_ms > 0 else ms_per_step
+    direct_flop = 2.0 * N * K * C * H * W * 9
+    value = direct_flop / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-stage timing in the same launch configuration (one launch = one slab)
+    tiles = -(-H // m) * (-(-W // m))
+    T_slab = slab_imgs * tiles
+    xs = xd[:slab_imgs].contiguous()
+    V = nova.nova_input_transform(t, xs)
+    M = nova.nova_contract(t, U, V, slab_imgs, C, H, W, K, flags)
+    ys = nova.nova_output_transform(t, M, slab_imgs, K, H, W, tdtype, flags)
+
+    def time_stage(fn, reps):
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps * 1e-3
+
+    reps = max(10, args.steps)
+    cb, kb = -(-C // 32) * 32, -(-K // 32) * 32
+    x_b = slab_imgs * C * H * W * es
+    y_b = slab_imgs * K * H * W * es
+    V_b = n * n * T_slab * cb * es
+    M_b = n * n * T_slab * kb * m_es
+    U_b = n * n * kb * cb * es
+    stages = {}
+    s_in = time_stage(lambda: nova.nova_input_transform(t, xs, V=V), reps)
+    stages["input_transform"] = dict(us=s_in * 1e6, bytes=x_b + V_b, gbs=(x_b + V_b) / s_in / 1e9)
+    s_c = time_stage(lambda: nova.nova_contract(t, U, V, slab_imgs, C, H, W, K, flags, M=M), reps)
+    gemm_flop = 2.0 * n * n * T_slab * C * K
+    stages["contract"] = dict(us=s_c * 1e6, bytes=U_b + V_b + M_b, gbs=(U_b + V_b + M_b) / s_c / 1e9,
+                              tflops=gemm_flop / s_c / 1e12, mfma_frac=gemm_flop / s_c / 1e12 / MFMA_F16_PEAK_TFLOPS)
+    s_out = time_stage(lambda: nova.nova_output_transform(t, M, slab_imgs, K, H, W, tdtype, flags, y=ys), reps)
+    stages["output_transform"] = dict(us=s_out * 1e6, bytes=M_b + y_b, gbs=(M_b + y_b) / s_out / 1e9)
+    for st in stages.values():
+        st["hbm_frac"] = st["gbs"] / HBM_PEAK_GBS
+    dominant = max(stages, key=lambda k: stages[k]["us"])
+    dom = stages[dominant]
+    roofline = dict(kernel=dominant, bound="hbm", achieved=round(dom["gbs"], 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(dom["gbs"] / HBM_PEAK_GBS, 4), traffic=None,
+                    launch_us=round(dom["us"], 2), algorithmic_bytes=dom["bytes"])
+
+    # ---- accuracy on sampled images and the CPU oracle leg
+    result_extra = {}
+    cpu_baseline = None
+    if not args.no_cpu:
+        from oracle import conv as oracle_conv
+        torch.cuda.synchronize()
+        w64 = w.astype(np.float64)
+        tic = time.perf_counter()
+        ref1 = oracle_conv.direct_conv2d(x[:1].astype(np.float64), w64)
+        per_img = time.perf_counter() - tic
+        n_cpu = int(min(N, max(1, round(12.0 / max(per_img, 1e-3)))))
+        tic = time.perf_counter()
+        ref = oracle_conv.direct_conv2d(x[:n_cpu].astype(np.float64), w64)
+        cpu_s = time.perf_counter() - tic
+        cpu_flop = 2.0 * n_cpu * K * C * H * W * 9
+        cpu_baseline = dict(value=round(cpu_flop / cpu_s / 1e12, 6), unit="TFLOP/s", cores=oracle_conv.threads(),
+                            kind="oracle", sample=f"fp64 direct conv of images 0..{n_cpu - 1} of {N} "
+                            f"({cpu_flop / 1e9:.1f} GFLOP in {cpu_s:.2f} s, OpenMP)")
+        got = y[:n_cpu].cpu().numpy().astype(np.float64)
+        fin = np.isfinite(got)
+        result_extra["nonfinite_frac"] = float(1.0 - fin.mean())
+        if fin.all():
+            result_extra["rel_l2_vs_fp64"] = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+            emu = oracle_conv.winograd_conv2d_emulated(x[:2].astype(np.float64), w64,
+                                                       [Fraction(a, b) for a, b in points], m,
+                                                       storage=16 if dt == nova.NOVA_F16 else 32,
+                                                       m_storage=16 if m_es == 2 else 32)
+            result_extra["rel_l2_vs_emulation"] = float(np.linalg.norm(got[:2] - emu) / np.linalg.norm(emu))
+        del ref1
+
+    out = {
+        "metric": "effective TFLOP/s (direct-conv FLOPs), F(8,3) VGG-16 3x3 layer",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16" if dt == nova.NOVA_F16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: 3x3 conv N={N} C={C} K={K} H=W={H}, F({m},3), {args.points} points",
+                   "points": args.points, "images_per_slab": int(slab_imgs), "slabs": int(n_slabs),
+                   "products_dtype": "f16" if m_es == 2 else "f32"},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "stages": {k: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()}
+                   for k, v in stages.items()},
+    }
+    out.update(result_extra)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,165 @@
+/*
+ * nova.h -- C ABI of libnova: 2D Winograd minimal-filtering convolution F(m x m, 3 x 3)
+ * on AMD CDNA4 (gfx950), with Cook-Toom transform matrices A, B^T, G generated exactly
+ * (rational arithmetic, host) from an arbitrary set of interpolation points.
+ *
+ * The algorithm (arxiv 2512.18453, Sec. 2.1 "Winograd Convolution via Cook-Toom", nested
+ * in 2D as in App. "2D Extension via Kronecker Products"):
+ *
+ *     Y = A^T [ (G g G^T) * (B^T d B) ] A,   summed over input channels before A^T . A,
+ *
+ * for each n x n input tile d (n = m + 2, tiles at stride m over the image zero-padded by
+ * one pixel) and each 3 x 3 filter g; stride 1, pad 1, correlation (no kernel flip), no bias.
+ *
+ * Conventions for every call
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP device memory
+ *     of the current device; nothing is copied between the two behind the caller's back.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Device work is
+ *     enqueued on it and the call returns without waiting.
+ *   - No call allocates or frees device memory, none keeps global state besides the last
+ *     HIP error code (thread-local).
+ *   - Return value: NOVA_OK (0) or a negative NOVA_E* code; nothing throws or aborts.
+ *   - dtype selects the storage format of x, w, U, V, y: NOVA_F16 (IEEE binary16) or
+ *     NOVA_F32.  Arithmetic: transforms in binary32 (filter transform in binary64),
+ *     channel contraction on the matrix cores with binary32 accumulation.
+ */
+#ifndef NOVA_H
+#define NOVA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct { int64_t num, den; } nova_rational;   /* den > 0 on output; den != 0 on input */
+typedef struct nova_transforms nova_transforms;       /* opaque, host memory, immutable */
+
+enum {
+    NOVA_OK = 0,
+    NOVA_EINVAL = -1,       /* null pointer, bad size, bad enum, zero denominator, wrong point count */
+    NOVA_EDUP = -2,         /* two equal interpolation points (singular Vandermonde system) */
+    NOVA_EOVERFLOW = -3,    /* an exact intermediate or matrix entry does not fit 64-bit num/den */
+    NOVA_EVERIFY = -4,      /* the generated matrices fail the exact tensor identity (internal bug trap) */
+    NOVA_ENOSPC = -5,       /* workspace too small */
+    NOVA_EUNSUPPORTED = -6, /* valid request the device path does not implement (m not in {2,4,6,8}, r != 3) */
+    NOVA_EHIP = -7,         /* a HIP call failed; see nova_last_hip_error() */
+    NOVA_ENOMEM = -8        /* host allocation failed */
+};
+
+enum { NOVA_F32 = 0, NOVA_F16 = 1 };
+enum { NOVA_MATRIX_A = 0, NOVA_MATRIX_BT = 1, NOVA_MATRIX_G = 2 };
+
+/* flags of nova_winograd_conv2d / nova_output_transform / nova_contract */
+enum {
+    NOVA_FLAG_RELU = 1,     /* y = max(y, 0) fused into the output transform (NaN stays NaN) */
+    NOVA_FLAG_M_F16 = 2     /* NOVA_F16 only: keep the products M in binary16 instead of binary32 */
+};
+
+/* ------------------------------------------------------------------ transforms (host) */
+
+/*
+ * Exact Cook-Toom construction (Alg. "Symbolic Cook-Toom Construction"; Sec. 2.4).
+ * finite_points: host array of n_points = m + r - 2 distinct rationals alpha_0 .. alpha_{n-2},
+ * n = m + r - 1; the point at infinity is implicit and always last.  Row p of every matrix
+ * belongs to alpha_p in the order given.
+ *   A   (n x m)  A[p][i]  = alpha_p^i;                       infinity row = e_{m-1}
+ *   G   (n x r)  G[p][k]  = alpha_p^k / F_p,  F_p = prod_{j != p} (alpha_p - alpha_j);   infinity row = e_{r-1}
+ *   B^T (n x n)  row p = coefficients (ascending powers) of prod_{j != p} (t - alpha_j), then 0;
+ *                infinity row = coefficients of prod_j (t - alpha_j)
+ * The result is verified against the exact identity sum_p A[p][i] B^T[p][j] G[p][k] = [j == i + k]
+ * before it is returned.  Any m >= 1, r >= 1 with n <= 16 is accepted here; the device calls
+ * below need r == 3 and m in {2, 4, 6, 8}.
+ * *out is owned by the caller: release with nova_free_transforms.
+ */
+int nova_make_transforms(const nova_rational *finite_points, int n_points, int m, int r,
+                         nova_transforms **out);
+void nova_free_transforms(nova_transforms *t);
+
+/* m, r, n of a handle; `symmetric` = 1 when the points come as 0, +a1, -a1, +a2, -a2, ...
+ * (the order for which the device transforms share work between +a and -a). Any pointer may be NULL. */
+int nova_transforms_shape(const nova_transforms *t, int *m, int *r, int *n, int *symmetric);
+
+/* Row-major copy of one matrix into caller-allocated host memory (n*m, n*n or n*r entries):
+ * exact (NOVA_EOVERFLOW if an entry needs more than 64 bits), or rounded once to the nearest
+ * binary64 / binary32 -- the tables the device code uses (B^T, A: binary32; G: binary64). */
+int nova_get_matrix(const nova_transforms *t, int which, nova_rational *out);
+int nova_get_matrix_f64(const nova_transforms *t, int which, double *out);
+int nova_get_matrix_f32(const nova_transforms *t, int which, float *out);
+
+/* Spectral condition numbers (Sec. 2.2 "Condition Number Definition"): out[0] = kappa_2 of the
+ * square Vandermonde matrix of the finite points, out[1..3] = kappa_2 of A, B^T, G. */
+int nova_kappa(const nova_transforms *t, double out[4]);
+
+/* ------------------------------------------------------------------ device tensors */
+
+/*
+ * Winograd-domain layouts (device, opaque to most callers; documented for tests).
+ * xi = i*n + j indexes the n*n transform-domain positions, t = (image*tiles_h + tile_row)*tiles_w
+ * + tile_col the tiles, tiles_h = ceil(H/m), tiles_w = ceil(W/m).  Channels are blocked by 32:
+ *   U [n*n][ceil(C/32)][Kp][32]   Kp = K rounded up to a multiple of 32; element (xi, k, c) at
+ *                                 ((xi*ceil(C/32) + c/32)*Kp + k)*32 + c%32; padding is zero
+ *   V [n*n][ceil(C/32)][T][32]    same with t in place of k and T in place of Kp
+ *   M [n*n][ceil(K/32)][T][32]    element (xi, t, k) at ((xi*ceil(K/32) + k/32)*T + t)*32 + k%32
+ * U and V have the storage dtype; M is binary32 (binary16 with NOVA_FLAG_M_F16).
+ */
+size_t nova_filter_bytes(int K, int C, int m, int dtype);                 /* size of U */
+size_t nova_input_bytes(int N, int C, int H, int W, int m, int dtype);    /* size of V, whole batch */
+size_t nova_product_bytes(int N, int K, int H, int W, int m, int dtype, int flags); /* size of M */
+
+/*
+ * Filter transform U = G g G^T (Sec. 2.1 step 2 in 2D), evaluated in binary64 and rounded once
+ * to dtype.  w: device [K][C][3][3] of dtype; U: device, nova_filter_bytes(K, C, m, dtype) bytes,
+ * fully overwritten (padding included).  Done once per weight set, off the per-call path.
+ */
+int nova_filter_transform(const nova_transforms *t, const void *w, int K, int C, int dtype,
+                          void *U, void *stream);
+
+/*
+ * Workspace for nova_winograd_conv2d.  The call processes the batch in slabs of whole images so
+ * that V and M of a slab stay cache resident; the slab size follows from the workspace it is
+ * given.  images_per_slab = 0 asks for the library's default (a slab of about 64 MiB), N for the
+ * whole batch in one pass.  Returns 0 for invalid arguments.
+ */
+size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K, int m, int dtype, int flags,
+                                   int images_per_slab);
+
+/*
+ * y = conv3x3(x, w), stride 1, pad 1, through F(m x m, 3 x 3) with the handle's matrices:
+ * input transform -> n*n channel contractions -> output transform, enqueued on `stream`.
+ * x: device [N][C][H][W]; U: from nova_filter_transform with the same handle, K, C, dtype;
+ * y: device [N][K][H][W]; all of dtype.  H, W >= 1 arbitrary: the image is zero-extended to
+ * whole tiles and the result cropped.  workspace: device, at least
+ * nova_conv2d_workspace_bytes(..., images_per_slab = 1) bytes, 256-byte aligned; must not
+ * overlap x, U, y.  Errors: NOVA_EINVAL, NOVA_EUNSUPPORTED, NOVA_ENOSPC, NOVA_EHIP.
+ * Arithmetic contract of the input transform (what makes V reproducible bit for bit): each 1D
+ * transform row is E + O in binary32, E / O = fused multiply-add chains over the even / odd
+ * input indices in ascending order; columns of the tile first, then rows.
+ */
+int nova_winograd_conv2d(const nova_transforms *t, const void *x, const void *U, void *y,
+                         int N, int C, int H, int W, int K, int dtype, int flags,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* The three stages on their own (same arguments; V, M: device buffers of nova_input_bytes /
+ * nova_product_bytes for the N images passed).  For tests and per-stage profiling. */
+int nova_input_transform(const nova_transforms *t, const void *x, void *V,
+                         int N, int C, int H, int W, int dtype, void *stream);        /* Sec. 2.1 step 1 */
+int nova_contract(const nova_transforms *t, const void *U, const void *V, void *M,
+                  int N, int C, int H, int W, int K, int dtype, int flags, void *stream); /* step 3 + channel sum */
+int nova_output_transform(const nova_transforms *t, const void *M, void *y,
+                          int N, int K, int H, int W, int dtype, int flags, void *stream); /* step 4 */
+
+/* out = maxpool2x2(max(in, 0)), stride 2, floor; in [N][C][H][W] -> out [N][C][H/2][W/2] (device).
+ * The step between the blocks of a VGG-style stack. */
+int nova_relu_maxpool2x2(const void *in, void *out, int N, int C, int H, int W, int dtype, void *stream);
+
+/* ------------------------------------------------------------------ misc */
+const char *nova_strerror(int code);
+int nova_last_hip_error(void);     /* hipError_t of the last failed HIP call on this thread, 0 if none */
+const char *nova_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NOVA_H */

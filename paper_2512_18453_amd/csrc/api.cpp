@@ -1,0 +1,178 @@
+// The device-facing entry points of libnova: argument checks, tensor geometry, the slab loop of
+// nova_winograd_conv2d.  All device work is done by the launchers in the .hip files.
+#include <cstring>
+
+#include "internal.hpp"
+
+namespace nova {
+
+static thread_local int g_last_hip_error = 0;
+void set_last_hip_error(int err) { g_last_hip_error = err; }
+
+static int hip_result(int err)
+{
+    if (err == 0) return NOVA_OK;
+    g_last_hip_error = err;
+    return NOVA_EHIP;
+}
+
+static bool device_tile_ok(int m) { return m == 2 || m == 4 || m == 6 || m == 8; }
+static bool dtype_ok(int dtype) { return dtype == NOVA_F16 || dtype == NOVA_F32; }
+
+static int check_handle(const nova_transforms *t)
+{
+    if (!t) return NOVA_EINVAL;
+    if (t->r != 3 || !device_tile_ok(t->m)) return NOVA_EUNSUPPORTED;
+    return NOVA_OK;
+}
+
+static bool dims_ok(int N, int C, int H, int W, int K)
+{
+    return N >= 1 && C >= 1 && H >= 1 && W >= 1 && K >= 1 && N <= (1 << 20) && C <= (1 << 20) &&
+           K <= (1 << 20) && H <= (1 << 16) && W <= (1 << 16);
+}
+
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+static size_t v_bytes(const Geometry &g, int dtype)
+{
+    return (size_t)g.n * g.n * g.c_blocks * (size_t)g.T * kChanBlock * dtype_size(dtype);
+}
+static size_t m_bytes(const Geometry &g, int dtype, int flags)
+{
+    const size_t es = (dtype == NOVA_F16 && (flags & NOVA_FLAG_M_F16)) ? 2 : 4;
+    return (size_t)g.n * g.n * g.k_blocks * (size_t)g.T * kChanBlock * es;
+}
+
+constexpr size_t kDefaultSlabBytes = (size_t)64 << 20;
+
+}  // namespace nova
+
+using namespace nova;
+
+extern "C" size_t nova_filter_bytes(int K, int C, int m, int dtype)
+{
+    if (K < 1 || C < 1 || m < 1 || !dtype_ok(dtype)) return 0;
+    const size_t n = (size_t)m + 2;
+    return n * n * ceil_div(C, kChanBlock) * ((size_t)ceil_div(K, kChanBlock) * kChanBlock) * kChanBlock *
+           dtype_size(dtype);
+}
+
+extern "C" size_t nova_input_bytes(int N, int C, int H, int W, int m, int dtype)
+{
+    if (!dims_ok(N, C, H, W, 1) || m < 1 || !dtype_ok(dtype)) return 0;
+    return v_bytes(make_geometry(N, C, H, W, 1, m), dtype);
+}
+
+extern "C" size_t nova_product_bytes(int N, int K, int H, int W, int m, int dtype, int flags)
+{
+    if (!dims_ok(N, 1, H, W, K) || m < 1 || !dtype_ok(dtype)) return 0;
+    return m_bytes(make_geometry(N, 1, H, W, K, m), dtype, flags);
+}
+
+extern "C" size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K, int m, int dtype, int flags,
+                                              int images_per_slab)
+{
+    if (!dims_ok(N, C, H, W, K) || !device_tile_ok(m) || !dtype_ok(dtype) || images_per_slab < 0) return 0;
+    const Geometry one = make_geometry(1, C, H, W, K, m);
+    const size_t per_image = align256(v_bytes(one, dtype)) + align256(m_bytes(one, dtype, flags));
+    long long imgs = images_per_slab;
+    if (imgs == 0) {
+        imgs = (long long)(kDefaultSlabBytes / per_image);
+        if (imgs < 1) imgs = 1;
+    }
+    if (imgs > N) imgs = N;
+    const Geometry slab = make_geometry((int)imgs, C, H, W, K, m);
+    return align256(v_bytes(slab, dtype)) + align256(m_bytes(slab, dtype, flags));
+}
+
+extern "C" int nova_filter_transform(const nova_transforms *t, const void *w, int K, int C, int dtype,
+                                     void *U, void *stream)
+{
+    if (int rc = check_handle(t)) return rc;
+    if (!w || !U || K < 1 || C < 1 || !dtype_ok(dtype)) return NOVA_EINVAL;
+    return hip_result(launch_filter_transform(t, w, K, C, dtype, U, stream));
+}
+
+extern "C" int nova_input_transform(const nova_transforms *t, const void *x, void *V, int N, int C, int H,
+                                    int W, int dtype, void *stream)
+{
+    if (int rc = check_handle(t)) return rc;
+    if (!x || !V || !dims_ok(N, C, H, W, 1) || !dtype_ok(dtype)) return NOVA_EINVAL;
+    return hip_result(launch_input_transform(t, x, V, make_geometry(N, C, H, W, 1, t->m), dtype, stream));
+}
+
+extern "C" int nova_contract(const nova_transforms *t, const void *U, const void *V, void *M, int N, int C,
+                             int H, int W, int K, int dtype, int flags, void *stream)
+{
+    if (int rc = check_handle(t)) return rc;
+    if (!U || !V || !M || !dims_ok(N, C, H, W, K) || !dtype_ok(dtype)) return NOVA_EINVAL;
+    return hip_result(launch_contract(t, U, V, M, make_geometry(N, C, H, W, K, t->m), dtype, flags, stream));
+}
+
+extern "C" int nova_output_transform(const nova_transforms *t, const void *M, void *y, int N, int K, int H,
+                                     int W, int dtype, int flags, void *stream)
+{
+    if (int rc = check_handle(t)) return rc;
+    if (!M || !y || !dims_ok(N, 1, H, W, K) || !dtype_ok(dtype)) return NOVA_EINVAL;
+    return hip_result(launch_output_transform(t, M, y, make_geometry(N, 1, H, W, K, t->m), dtype, flags, stream));
+}
+
+extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, const void *U, void *y, int N,
+                                    int C, int H, int W, int K, int dtype, int flags, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    if (int rc = check_handle(t)) return rc;
+    if (!x || !U || !y || !workspace || !dims_ok(N, C, H, W, K) || !dtype_ok(dtype)) return NOVA_EINVAL;
+    if (((uintptr_t)workspace & 255) != 0) return NOVA_EINVAL;
+    const int m = t->m;
+
+    // largest slab (whole images) whose V and M fit the workspace
+    const Geometry one = make_geometry(1, C, H, W, K, m);
+    const size_t v1 = v_bytes(one, dtype), m1 = m_bytes(one, dtype, flags);
+    if (align256(v1) + align256(m1) > workspace_bytes) return NOVA_ENOSPC;
+    long long imgs = (long long)(workspace_bytes / (v1 + m1));
+    if (imgs < 1) imgs = 1;
+    if (imgs > N) imgs = N;
+    while (imgs > 1 && align256(v1 * imgs) + align256(m1 * imgs) > workspace_bytes) --imgs;
+
+    const size_t es = dtype_size(dtype);
+    char *Vbuf = (char *)workspace;
+    char *Mbuf = Vbuf + align256(v1 * (size_t)imgs);
+    for (int n0 = 0; n0 < N; n0 += (int)imgs) {
+        const int nb = (N - n0 < imgs) ? N - n0 : (int)imgs;
+        const Geometry g = make_geometry(nb, C, H, W, K, m);
+        const char *xs = (const char *)x + (size_t)n0 * C * H * W * es;
+        char *ys = (char *)y + (size_t)n0 * K * H * W * es;
+        if (int err = launch_input_transform(t, xs, Vbuf, g, dtype, stream)) return hip_result(err);
+        if (int err = launch_contract(t, U, Vbuf, Mbuf, g, dtype, flags, stream)) return hip_result(err);
+        if (int err = launch_output_transform(t, Mbuf, ys, g, dtype, flags, stream)) return hip_result(err);
+    }
+    return NOVA_OK;
+}
+
+extern "C" int nova_relu_maxpool2x2(const void *in, void *out, int N, int C, int H, int W, int dtype,
+                                    void *stream)
+{
+    if (!in || !out || !dims_ok(N, C, H, W, 1) || !dtype_ok(dtype)) return NOVA_EINVAL;
+    return hip_result(launch_relu_maxpool2x2(in, out, N, C, H, W, dtype, stream));
+}
+
+extern "C" const char *nova_strerror(int code)
+{
+    switch (code) {
+    case NOVA_OK: return "ok";
+    case NOVA_EINVAL: return "invalid argument";
+    case NOVA_EDUP: return "duplicate interpolation point";
+    case NOVA_EOVERFLOW: return "exact arithmetic overflowed 64-bit numerator/denominator";
+    case NOVA_EVERIFY: return "generated transforms fail the exact tensor identity";
+    case NOVA_ENOSPC: return "workspace too small";
+    case NOVA_EUNSUPPORTED: return "unsupported tile size or kernel size for the device path";
+    case NOVA_EHIP: return "HIP call failed (see nova_last_hip_error)";
+    case NOVA_ENOMEM: return "out of host memory";
+    default: return "unknown error";
+    }
+}
+
+extern "C" int nova_last_hip_error(void) { return g_last_hip_error; }
+extern "C" const char *nova_version(void) { return "libnova 0.1 (gfx950)"; }

@@ -1,0 +1,52 @@
+// Device-side helpers shared by the libnova kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include "internal.hpp"
+
+namespace nova {
+
+typedef _Float16 f16;
+
+// storage <-> binary32; the binary16 conversion rounds to nearest even, keeps sub-normals and
+// overflows to infinity (v_cvt_f16_f32).
+__device__ __forceinline__ float load_f32(const float *p) { return *p; }
+__device__ __forceinline__ float load_f32(const f16 *p) { return (float)*p; }
+__device__ __forceinline__ void store_from_f32(float *p, float v) { *p = v; }
+__device__ __forceinline__ void store_from_f32(f16 *p, float v) { *p = (f16)v; }
+
+__device__ __forceinline__ float fma32(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+
+// binary64 -> storage with a single rounding.  For binary16 the value first goes to binary32
+// with round-to-odd (the inexact bit survives in the last place), after which the
+// round-to-nearest-even conversion to binary16 cannot double round (24 >= 11 + 2 bits).
+__device__ __forceinline__ float round_f64_to(double v, float *) { return (float)v; }
+__device__ __forceinline__ f16 round_f64_to(double v, f16 *)
+{
+    float f = (float)v;                           // nearest even
+    if (!(__builtin_fabs(v) <= 3.0e38) || (double)f == v) return (f16)f;   // exact, huge, inf or NaN
+    unsigned bits = __float_as_uint(f);
+    bool away = __builtin_fabs((double)f) > __builtin_fabs(v);   // rounded away from zero?
+    if (away) bits -= 1;                          // step back to the truncated magnitude
+    bits |= 1u;                                   // inexact: force the last place odd
+    return (f16)__uint_as_float(bits);
+}
+
+// blockIdx.x -> logical block id such that consecutive logical ids run on the same XCD
+// (hardware deals consecutive workgroup ids round-robin over the 8 XCDs, each with its own L2).
+__device__ __forceinline__ unsigned xcd_local_block_id(unsigned id, unsigned total)
+{
+    constexpr unsigned kXcd = 8;
+    unsigned full = total / kXcd * kXcd;
+    if (id >= full) return id;                    // ragged tail: leave as is
+    return (id % kXcd) * (total / kXcd) + id / kXcd;
+}
+
+}  // namespace nova
+
+#define NOVA_HIP_TRY(expr)                                   \
+    do {                                                     \
+        hipError_t nova_err_ = (expr);                       \
+        if (nova_err_ != hipSuccess) return (int)nova_err_;  \
+    } while (0)

@@ -1,0 +1,99 @@
+// Shared between the host-side pieces of libnova: the transform handle, the coefficient
+// packs handed to kernels by value, tensor geometry, and the launcher prototypes.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "../../include/nova.h"
+#include "rational.hpp"
+
+namespace nova {
+
+constexpr int kChanBlock = 32;   // channel blocking of U, V, M
+constexpr int kMaxN = 16;        // largest n = m + r - 1 nova_make_transforms accepts
+
+// Coefficients of one 1D input transform, n = N.
+//   generic: the whole B^T, row-major.
+//   symmetric (points 0, +a1, -a1, ...; H = (N-2)/2 pairs):
+//     zero[H+1]  row of the point 0: coefficients at the even positions 0, 2, .., 2H
+//     ev[j][H]   row of +a_j: coefficients at the even positions 2, 4, .., 2H
+//     od[j][H]   row of +a_j: coefficients at the odd positions 1, 3, .., 2H-1
+//     inf[H+1]   row of infinity: coefficients at the odd positions 1, 3, .., 2H+1
+//   (all other entries of those rows are exactly zero, the row of -a_j has the same even and
+//   the negated odd coefficients)
+template <int N>
+struct InCoef {
+    static constexpr int H = (N - 2) / 2;
+    float bt[N * N];
+    float zero[H + 1];
+    float ev[H > 0 ? H * H : 1];
+    float od[H > 0 ? H * H : 1];
+    float inf[H + 1];
+};
+
+// Coefficients of one 1D output transform: A (N x M) row-major, and for the symmetric case
+// pw[j][i] = a_j^i.
+template <int N>
+struct OutCoef {
+    static constexpr int M = N - 2;
+    static constexpr int H = (N - 2) / 2;
+    float a[N * M];
+    float pw[H > 0 ? H * M : 1];
+};
+
+template <int N>
+struct FilterCoef {
+    double g[N * 3];
+};
+
+struct Geometry {
+    int N, C, H, W, K, m, n;
+    int tiles_h, tiles_w;
+    long long T;          // tiles in the batch
+    int c_blocks, k_blocks;
+    int Kp;               // K rounded up to the channel block
+};
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+inline Geometry make_geometry(int N, int C, int H, int W, int K, int m)
+{
+    Geometry g;
+    g.N = N; g.C = C; g.H = H; g.W = W; g.K = K; g.m = m; g.n = m + 2;
+    g.tiles_h = ceil_div(H, m);
+    g.tiles_w = ceil_div(W, m);
+    g.T = (long long)N * g.tiles_h * g.tiles_w;
+    g.c_blocks = ceil_div(C, kChanBlock);
+    g.k_blocks = ceil_div(K, kChanBlock);
+    g.Kp = g.k_blocks * kChanBlock;
+    return g;
+}
+
+inline size_t dtype_size(int dtype) { return dtype == NOVA_F16 ? 2 : 4; }
+
+}  // namespace nova
+
+struct nova_transforms {
+    int m = 0, r = 0, n = 0;
+    bool symmetric = false;
+    std::vector<nova::Rat> points, A, BT, G;   // exact, row-major
+    std::vector<double> A64, BT64, G64;        // rounded once
+    std::vector<float> A32, BT32, G32;
+};
+
+// ---- kernel launchers (defined in the .hip files); all return a hipError_t as int ----
+namespace nova {
+void set_last_hip_error(int err);
+
+int launch_filter_transform(const nova_transforms *t, const void *w, int K, int C, int dtype,
+                            void *U, void *stream);
+int launch_input_transform(const nova_transforms *t, const void *x, void *V, const Geometry &g,
+                           int dtype, void *stream);
+int launch_contract(const nova_transforms *t, const void *U, const void *V, void *M,
+                    const Geometry &g, int dtype, int flags, void *stream);
+int launch_output_transform(const nova_transforms *t, const void *M, void *y, const Geometry &g,
+                            int dtype, int flags, void *stream);
+int launch_relu_maxpool2x2(const void *in, void *out, int N, int C, int H, int W, int dtype,
+                           void *stream);
+}  // namespace nova

@@ -1,0 +1,259 @@
+// Host side of libnova: exact Cook-Toom construction of A, B^T, G from interpolation points
+// (Alg. "Symbolic Cook-Toom Construction"), exact verification of the bilinear identity
+// (Sec. 2.4), rounded tables, and spectral condition numbers (Sec. 2.2).
+#include <algorithm>
+#include <cmath>
+#include <new>
+
+#include "internal.hpp"
+
+using nova::Rat;
+using nova::RatCtx;
+
+namespace {
+
+// prod_j (t - roots[j]) as ascending coefficients, skipping index `skip` (-1: none)
+std::vector<Rat> expand_roots(RatCtx &cx, const std::vector<Rat> &roots, int skip)
+{
+    std::vector<Rat> poly(1);
+    poly[0] = cx.make(1, 1);
+    for (int j = 0; j < (int)roots.size(); ++j) {
+        if (j == skip) continue;
+        std::vector<Rat> next(poly.size() + 1);
+        for (size_t d = 0; d < poly.size(); ++d) {
+            next[d + 1] = cx.add(next[d + 1], poly[d]);
+            next[d] = cx.sub(next[d], cx.mul(roots[j], poly[d]));
+        }
+        poly.swap(next);
+    }
+    return poly;
+}
+
+Rat power(RatCtx &cx, const Rat &base, int e)
+{
+    Rat r = cx.make(1, 1);
+    for (int i = 0; i < e; ++i) r = cx.mul(r, base);
+    return r;
+}
+
+// sum_p A[p][i] BT[p][j] G[p][k] == [j == i + k] for all i, j, k, exactly
+bool identity_holds(RatCtx &cx, const nova_transforms &t)
+{
+    for (int i = 0; i < t.m; ++i)
+        for (int j = 0; j < t.n; ++j)
+            for (int k = 0; k < t.r; ++k) {
+                Rat sum = cx.make(0, 1);
+                for (int p = 0; p < t.n; ++p)
+                    sum = cx.add(sum, cx.mul(cx.mul(t.A[p * t.m + i], t.BT[p * t.n + j]), t.G[p * t.r + k]));
+                Rat want = cx.make(j == i + k ? 1 : 0, 1);
+                if (!cx.ok || !RatCtx::eq(sum, want)) return false;
+            }
+    return true;
+}
+
+// Singular values by one-sided Jacobi rotations on the columns (rows >= cols), descending.
+std::vector<double> singular_values(std::vector<double> a, int rows, int cols)
+{
+    for (int sweep = 0; sweep < 60; ++sweep) {
+        double off = 0.0;
+        for (int p = 0; p < cols - 1; ++p)
+            for (int q = p + 1; q < cols; ++q) {
+                double app = 0, aqq = 0, apq = 0;
+                for (int i = 0; i < rows; ++i) {
+                    app += a[i * cols + p] * a[i * cols + p];
+                    aqq += a[i * cols + q] * a[i * cols + q];
+                    apq += a[i * cols + p] * a[i * cols + q];
+                }
+                if (apq == 0.0) continue;
+                off = std::max(off, std::fabs(apq) / std::sqrt(app * aqq));
+                double zeta = (aqq - app) / (2.0 * apq);
+                double tn = (zeta >= 0 ? 1.0 : -1.0) / (std::fabs(zeta) + std::sqrt(1.0 + zeta * zeta));
+                double cs = 1.0 / std::sqrt(1.0 + tn * tn), sn = cs * tn;
+                for (int i = 0; i < rows; ++i) {
+                    double vp = a[i * cols + p], vq = a[i * cols + q];
+                    a[i * cols + p] = cs * vp - sn * vq;
+                    a[i * cols + q] = sn * vp + cs * vq;
+                }
+            }
+        if (off < 1e-15) break;
+    }
+    std::vector<double> sv(cols);
+    for (int j = 0; j < cols; ++j) {
+        double s = 0;
+        for (int i = 0; i < rows; ++i) s += a[i * cols + j] * a[i * cols + j];
+        sv[j] = std::sqrt(s);
+    }
+    std::sort(sv.begin(), sv.end(), [](double x, double y) { return x > y; });
+    return sv;
+}
+
+double kappa2(const std::vector<double> &mat, int rows, int cols)
+{
+    std::vector<double> a = mat;
+    if (rows < cols) {   // transpose so that rows >= cols
+        std::vector<double> tr((size_t)rows * cols);
+        for (int i = 0; i < rows; ++i)
+            for (int j = 0; j < cols; ++j) tr[(size_t)j * rows + i] = mat[(size_t)i * cols + j];
+        a.swap(tr);
+        std::swap(rows, cols);
+    }
+    std::vector<double> sv = singular_values(a, rows, cols);
+    return sv.front() / sv.back();
+}
+
+const std::vector<Rat> *pick(const nova_transforms *t, int which, int *rows, int *cols)
+{
+    switch (which) {
+    case NOVA_MATRIX_A: *rows = t->n; *cols = t->m; return &t->A;
+    case NOVA_MATRIX_BT: *rows = t->n; *cols = t->n; return &t->BT;
+    case NOVA_MATRIX_G: *rows = t->n; *cols = t->r; return &t->G;
+    default: return nullptr;
+    }
+}
+
+}  // namespace
+
+extern "C" int nova_make_transforms(const nova_rational *finite_points, int n_points, int m, int r,
+                                    nova_transforms **out)
+{
+    if (!out) return NOVA_EINVAL;
+    *out = nullptr;
+    if (!finite_points || m < 1 || r < 1) return NOVA_EINVAL;
+    const int n = m + r - 1;
+    if (n > nova::kMaxN || n_points != n - 1) return NOVA_EINVAL;
+
+    RatCtx cx;
+    nova_transforms *t = new (std::nothrow) nova_transforms;
+    if (!t) return NOVA_ENOMEM;
+    t->m = m; t->r = r; t->n = n;
+    for (int p = 0; p < n - 1; ++p) {
+        if (finite_points[p].den == 0 || finite_points[p].num == INT64_MIN || finite_points[p].den == INT64_MIN) {
+            delete t;
+            return NOVA_EINVAL;
+        }
+        t->points.push_back(cx.make(finite_points[p].num, finite_points[p].den));
+    }
+    for (int p = 0; p < n - 1; ++p)
+        for (int q = p + 1; q < n - 1; ++q)
+            if (RatCtx::eq(t->points[p], t->points[q])) { delete t; return NOVA_EDUP; }
+
+    t->A.assign((size_t)n * m, cx.make(0, 1));
+    t->G.assign((size_t)n * r, cx.make(0, 1));
+    t->BT.assign((size_t)n * n, cx.make(0, 1));
+    for (int p = 0; p < n - 1; ++p) {
+        const Rat &alpha = t->points[p];
+        Rat F = cx.make(1, 1);                       // Lagrange factor prod_{j != p} (alpha_p - alpha_j)
+        for (int j = 0; j < n - 1; ++j)
+            if (j != p) F = cx.mul(F, cx.sub(alpha, t->points[j]));
+        Rat Finv = cx.inv(F);
+        for (int i = 0; i < m; ++i) t->A[(size_t)p * m + i] = power(cx, alpha, i);
+        for (int k = 0; k < r; ++k) t->G[(size_t)p * r + k] = cx.mul(power(cx, alpha, k), Finv);
+        std::vector<Rat> Np = expand_roots(cx, t->points, p);   // degree n-2: n-1 coefficients
+        for (int j = 0; j < n - 1; ++j) t->BT[(size_t)p * n + j] = Np[j];
+    }
+    t->A[(size_t)(n - 1) * m + (m - 1)] = cx.make(1, 1);
+    t->G[(size_t)(n - 1) * r + (r - 1)] = cx.make(1, 1);
+    std::vector<Rat> Mt = expand_roots(cx, t->points, -1);       // degree n-1: n coefficients
+    for (int j = 0; j < n; ++j) t->BT[(size_t)(n - 1) * n + j] = Mt[j];
+
+    if (!cx.ok) { delete t; return NOVA_EOVERFLOW; }
+    for (const std::vector<Rat> *mat : {&t->A, &t->BT, &t->G})
+        for (const Rat &e : *mat)
+            if (!RatCtx::fits64(e)) { delete t; return NOVA_EOVERFLOW; }
+    if (!identity_holds(cx, *t)) {
+        int rc = cx.ok ? NOVA_EVERIFY : NOVA_EOVERFLOW;
+        delete t;
+        return rc;
+    }
+
+    // canonical symmetric order: 0, +a1, -a1, +a2, -a2, ...
+    bool sym = (n - 1) % 2 == 1 && RatCtx::is_zero(t->points[0]);
+    for (int j = 1; sym && j + 1 < n - 1; j += 2)
+        sym = RatCtx::eq(t->points[j], cx.neg(t->points[j + 1]));
+    // the device kernels rely on what symmetry implies for the matrices; confirm it exactly
+    for (int j = 1; sym && j + 1 < n - 1; j += 2)
+        for (int a = 0; a < n; ++a) {
+            const Rat &plus = t->BT[(size_t)j * n + a], &minus = t->BT[(size_t)(j + 1) * n + a];
+            sym = sym && RatCtx::eq(minus, (a % 2 == 0) ? plus : cx.neg(plus));
+            if (a == 0 || a == n - 1) sym = sym && RatCtx::is_zero(plus);
+            if (a < m) {
+                const Rat &ap = t->A[(size_t)j * m + a], &am = t->A[(size_t)(j + 1) * m + a];
+                sym = sym && RatCtx::eq(am, (a % 2 == 0) ? ap : cx.neg(ap));
+            }
+        }
+    for (int a = 0; sym && a < n; ++a) {
+        if (a % 2 == 1) sym = RatCtx::is_zero(t->BT[a]);                           // row of 0: even polynomial
+        else sym = RatCtx::is_zero(t->BT[(size_t)(n - 1) * n + a]);                 // row of infinity: odd
+        if (a >= 1 && a < m) sym = sym && RatCtx::is_zero(t->A[a]);                // A row of 0 = e_0
+    }
+    t->symmetric = sym;
+
+    for (const Rat &e : t->A) { t->A64.push_back(nova::rat_to_f64(e)); t->A32.push_back(nova::rat_to_f32(e)); }
+    for (const Rat &e : t->BT) { t->BT64.push_back(nova::rat_to_f64(e)); t->BT32.push_back(nova::rat_to_f32(e)); }
+    for (const Rat &e : t->G) { t->G64.push_back(nova::rat_to_f64(e)); t->G32.push_back(nova::rat_to_f32(e)); }
+    *out = t;
+    return NOVA_OK;
+}
+
+extern "C" void nova_free_transforms(nova_transforms *t) { delete t; }
+
+extern "C" int nova_transforms_shape(const nova_transforms *t, int *m, int *r, int *n, int *symmetric)
+{
+    if (!t) return NOVA_EINVAL;
+    if (m) *m = t->m;
+    if (r) *r = t->r;
+    if (n) *n = t->n;
+    if (symmetric) *symmetric = t->symmetric ? 1 : 0;
+    return NOVA_OK;
+}
+
+extern "C" int nova_get_matrix(const nova_transforms *t, int which, nova_rational *out)
+{
+    int rows, cols;
+    if (!t || !out) return NOVA_EINVAL;
+    const std::vector<Rat> *mat = pick(t, which, &rows, &cols);
+    if (!mat) return NOVA_EINVAL;
+    for (size_t i = 0; i < mat->size(); ++i) {
+        out[i].num = (int64_t)(*mat)[i].num;   // fits: checked at construction
+        out[i].den = (int64_t)(*mat)[i].den;
+    }
+    return NOVA_OK;
+}
+
+extern "C" int nova_get_matrix_f64(const nova_transforms *t, int which, double *out)
+{
+    if (!t || !out) return NOVA_EINVAL;
+    const std::vector<double> *src = which == NOVA_MATRIX_A ? &t->A64 : which == NOVA_MATRIX_BT ? &t->BT64
+                                   : which == NOVA_MATRIX_G ? &t->G64 : nullptr;
+    if (!src) return NOVA_EINVAL;
+    std::copy(src->begin(), src->end(), out);
+    return NOVA_OK;
+}
+
+extern "C" int nova_get_matrix_f32(const nova_transforms *t, int which, float *out)
+{
+    if (!t || !out) return NOVA_EINVAL;
+    const std::vector<float> *src = which == NOVA_MATRIX_A ? &t->A32 : which == NOVA_MATRIX_BT ? &t->BT32
+                                  : which == NOVA_MATRIX_G ? &t->G32 : nullptr;
+    if (!src) return NOVA_EINVAL;
+    std::copy(src->begin(), src->end(), out);
+    return NOVA_OK;
+}
+
+extern "C" int nova_kappa(const nova_transforms *t, double out[4])
+{
+    if (!t || !out) return NOVA_EINVAL;
+    const int nf = t->n - 1;
+    std::vector<double> V((size_t)nf * nf);
+    for (int p = 0; p < nf; ++p) {
+        double alpha = nova::rat_to_f64(t->points[p]), pw = 1.0;
+        // powers from the exact point: alpha^j rounded once would need the rational power; the
+        // product of correctly rounded factors is accurate to a few ulp, ample for kappa
+        for (int j = 0; j < nf; ++j) { V[(size_t)p * nf + j] = pw; pw *= alpha; }
+    }
+    out[0] = nf > 0 ? kappa2(V, nf, nf) : 1.0;
+    out[1] = kappa2(t->A64, t->n, t->m);
+    out[2] = kappa2(t->BT64, t->n, t->n);
+    out[3] = kappa2(t->G64, t->n, t->r);
+    return NOVA_OK;
+}

@@ -1,0 +1,241 @@
+"""Thin binding over libnova.so (include/nova.h): argument marshalling only.
+
+Every function has the name of the C entry point it calls.  Torch tensors are used as
+device-memory handles (`data_ptr()`) and for the current stream; all arithmetic runs in the
+library's kernels.  There is no fallback: if the library is missing the import of this module
+succeeds but the first call raises.
+"""
+import ctypes
+import os
+from fractions import Fraction
+
+import torch
+
+NOVA_F32, NOVA_F16 = 0, 1
+NOVA_MATRIX_A, NOVA_MATRIX_BT, NOVA_MATRIX_G = 0, 1, 2
+NOVA_FLAG_RELU, NOVA_FLAG_M_F16 = 1, 2
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnova.so")
+_lib = None
+
+EXPORTS = [
+    "nova_make_transforms", "nova_free_transforms", "nova_transforms_shape", "nova_get_matrix",
+    "nova_get_matrix_f64", "nova_get_matrix_f32", "nova_kappa", "nova_filter_bytes", "nova_input_bytes",
+    "nova_product_bytes", "nova_filter_transform", "nova_conv2d_workspace_bytes", "nova_winograd_conv2d",
+    "nova_input_transform", "nova_contract", "nova_output_transform", "nova_relu_maxpool2x2",
+    "nova_strerror", "nova_last_hip_error", "nova_version",
+]
+
+
+class nova_rational(ctypes.Structure):
+    _fields_ = [("num", ctypes.c_int64), ("den", ctypes.c_int64)]
+
+
+class NovaError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        detail = lib().nova_strerror(code).decode()
+        if code == -7:
+            detail += f" [hipError {lib().nova_last_hip_error()}]"
+        super().__init__(f"{where}: {detail} ({code})")
+
+
+def lib():
+    """The loaded library; raises if it has not been built (python -m paper_2512_18453_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} not found: build it with `python -m paper_2512_18453_amd.build`")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        ip = ctypes.POINTER(ctypes.c_int)
+        L.nova_make_transforms.argtypes = [ctypes.POINTER(nova_rational), i, i, i, ctypes.POINTER(vp)]
+        L.nova_free_transforms.argtypes = [vp]
+        L.nova_free_transforms.restype = None
+        L.nova_transforms_shape.argtypes = [vp, ip, ip, ip, ip]
+        L.nova_get_matrix.argtypes = [vp, i, ctypes.POINTER(nova_rational)]
+        L.nova_get_matrix_f64.argtypes = [vp, i, ctypes.POINTER(ctypes.c_double)]
+        L.nova_get_matrix_f32.argtypes = [vp, i, ctypes.POINTER(ctypes.c_float)]
+        L.nova_kappa.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
+        L.nova_filter_bytes.argtypes = [i, i, i, i]
+        L.nova_filter_bytes.restype = sz
+        L.nova_input_bytes.argtypes = [i] * 6
+        L.nova_input_bytes.restype = sz
+        L.nova_product_bytes.argtypes = [i] * 7
+        L.nova_product_bytes.restype = sz
+        L.nova_conv2d_workspace_bytes.argtypes = [i] * 9
+        L.nova_conv2d_workspace_bytes.restype = sz
+        L.nova_filter_transform.argtypes = [vp, vp, i, i, i, vp, vp]
+        L.nova_winograd_conv2d.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp]
+        L.nova_input_transform.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+        L.nova_contract.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        L.nova_output_transform.argtypes = [vp, vp, vp, i, i, i, i, i, i, vp]
+        L.nova_relu_maxpool2x2.argtypes = [vp, vp, i, i, i, i, i, vp]
+        L.nova_strerror.argtypes = [i]
+        L.nova_strerror.restype = ctypes.c_char_p
+        L.nova_last_hip_error.restype = i
+        L.nova_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(code, where):
+    if code != 0:
+        raise NovaError(code, where)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float16:
+        return NOVA_F16
+    if t.dtype == torch.float32:
+        return NOVA_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class Transforms:
+    """Owner of a nova_transforms handle."""
+
+    def __init__(self, handle, m, r, n, symmetric):
+        self.handle, self.m, self.r, self.n, self.symmetric = handle, m, r, n, symmetric
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.nova_free_transforms(self.handle)
+            self.handle = None
+
+
+def nova_make_transforms(points, m, r=3):
+    """points: finite interpolation points as ints, Fractions or (num, den) pairs."""
+    arr = (nova_rational * max(len(points), 1))()
+    for idx, p in enumerate(points):
+        if isinstance(p, tuple):
+            arr[idx].num, arr[idx].den = p
+        else:
+            fr = Fraction(p)
+            arr[idx].num, arr[idx].den = fr.numerator, fr.denominator
+    handle = ctypes.c_void_p()
+    _check(lib().nova_make_transforms(arr, len(points), m, r, ctypes.byref(handle)), "nova_make_transforms")
+    mm, rr, nn, sym = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(lib().nova_transforms_shape(handle, mm, rr, nn, sym), "nova_transforms_shape")
+    return Transforms(handle, mm.value, rr.value, nn.value, bool(sym.value))
+
+
+def _matrix_shape(t, which):
+    return (t.n, {NOVA_MATRIX_A: t.m, NOVA_MATRIX_BT: t.n, NOVA_MATRIX_G: t.r}[which])
+
+
+def nova_get_matrix(t, which):
+    rows, cols = _matrix_shape(t, which)
+    buf = (nova_rational * (rows * cols))()
+    _check(lib().nova_get_matrix(t.handle, which, buf), "nova_get_matrix")
+    return [[Fraction(buf[i * cols + j].num, buf[i * cols + j].den) for j in range(cols)] for i in range(rows)]
+
+
+def nova_get_matrix_f64(t, which):
+    rows, cols = _matrix_shape(t, which)
+    buf = (ctypes.c_double * (rows * cols))()
+    _check(lib().nova_get_matrix_f64(t.handle, which, buf), "nova_get_matrix_f64")
+    return [[buf[i * cols + j] for j in range(cols)] for i in range(rows)]
+
+
+def nova_get_matrix_f32(t, which):
+    rows, cols = _matrix_shape(t, which)
+    buf = (ctypes.c_float * (rows * cols))()
+    _check(lib().nova_get_matrix_f32(t.handle, which, buf), "nova_get_matrix_f32")
+    return [[buf[i * cols + j] for j in range(cols)] for i in range(rows)]
+
+
+def nova_kappa(t):
+    out = (ctypes.c_double * 4)()
+    _check(lib().nova_kappa(t.handle, out), "nova_kappa")
+    return dict(V=out[0], A=out[1], B=out[2], G=out[3])
+
+
+def nova_filter_bytes(K, C, m, dtype):
+    return lib().nova_filter_bytes(K, C, m, dtype)
+
+
+def nova_input_bytes(N, C, H, W, m, dtype):
+    return lib().nova_input_bytes(N, C, H, W, m, dtype)
+
+
+def nova_product_bytes(N, K, H, W, m, dtype, flags=0):
+    return lib().nova_product_bytes(N, K, H, W, m, dtype, flags)
+
+
+def nova_conv2d_workspace_bytes(N, C, H, W, K, m, dtype, flags=0, images_per_slab=0):
+    return lib().nova_conv2d_workspace_bytes(N, C, H, W, K, m, dtype, flags, images_per_slab)
+
+
+def nova_filter_transform(t, w, U=None):
+    """w [K,C,3,3] device tensor -> U (flat device tensor of the same dtype)."""
+    K, C = w.shape[0], w.shape[1]
+    dt = _dtype_code(w)
+    if U is None:
+        U = torch.empty(nova_filter_bytes(K, C, t.m, dt) // w.element_size(), dtype=w.dtype, device=w.device)
+    _check(lib().nova_filter_transform(t.handle, _dev(w), K, C, dt, _dev(U), _stream()), "nova_filter_transform")
+    return U
+
+
+def nova_winograd_conv2d(t, x, U, K, y=None, flags=0, workspace=None, images_per_slab=0):
+    """x [N,C,H,W] -> y [N,K,H,W]; workspace: uint8 device tensor (allocated here if None)."""
+    N, C, H, W = x.shape
+    dt = _dtype_code(x)
+    if y is None:
+        y = torch.empty((N, K, H, W), dtype=x.dtype, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(nova_conv2d_workspace_bytes(N, C, H, W, K, t.m, dt, flags, images_per_slab),
+                                dtype=torch.uint8, device=x.device)
+    _check(lib().nova_winograd_conv2d(t.handle, _dev(x), _dev(U), _dev(y), N, C, H, W, K, dt, flags,
+                                      _dev(workspace), workspace.numel(), _stream()), "nova_winograd_conv2d")
+    return y
+
+
+def nova_input_transform(t, x, V=None):
+    N, C, H, W = x.shape
+    dt = _dtype_code(x)
+    if V is None:
+        V = torch.empty(nova_input_bytes(N, C, H, W, t.m, dt) // x.element_size(), dtype=x.dtype, device=x.device)
+    _check(lib().nova_input_transform(t.handle, _dev(x), _dev(V), N, C, H, W, dt, _stream()), "nova_input_transform")
+    return V
+
+
+def nova_contract(t, U, V, N, C, H, W, K, flags=0, M=None):
+    dt = _dtype_code(V)
+    if M is None:
+        m_dtype = torch.float16 if (dt == NOVA_F16 and flags & NOVA_FLAG_M_F16) else torch.float32
+        nbytes = nova_product_bytes(N, K, H, W, t.m, dt, flags)
+        M = torch.empty(nbytes // (2 if m_dtype == torch.float16 else 4), dtype=m_dtype, device=V.device)
+    _check(lib().nova_contract(t.handle, _dev(U), _dev(V), _dev(M), N, C, H, W, K, dt, flags, _stream()), "nova_contract")
+    return M
+
+
+def nova_output_transform(t, M, N, K, H, W, dtype, flags=0, y=None):
+    """dtype: torch dtype of y (the storage format of the layer)."""
+    dt = NOVA_F16 if dtype == torch.float16 else NOVA_F32
+    if y is None:
+        y = torch.empty((N, K, H, W), dtype=dtype, device=M.device)
+    _check(lib().nova_output_transform(t.handle, _dev(M), _dev(y), N, K, H, W, dt, flags, _stream()), "nova_output_transform")
+    return y
+
+
+def nova_relu_maxpool2x2(x, out=None):
+    N, C, H, W = x.shape
+    if out is None:
+        out = torch.empty((N, C, H // 2, W // 2), dtype=x.dtype, device=x.device)
+    _check(lib().nova_relu_maxpool2x2(_dev(x), _dev(out), N, C, H, W, _dtype_code(x), _stream()), "nova_relu_maxpool2x2")
+    return out
+
+
+def nova_version():
+    return lib().nova_version().decode()

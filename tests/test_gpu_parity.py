@@ -1,0 +1,253 @@
+"""GPU parity: every stage of the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.
+
+Bars
+  U (filter transform)   bit-exact (fp64 evaluation, one rounding, on both sides)
+  V (input transform)    bit-exact (both sides follow the same binary32 operation order)
+  M, y in fp16 storage   rel-L2 <= 5e-3 against the oracle's fp16-storage emulation
+  y in fp32 storage      F(4,3) small layer: rel-L2 <= 1e-5 and max-abs <= 1e-4 against the fp64
+                         definition; other tiles: within 4x the emulation's own distance from the
+                         fp64 definition (the GPU adds fp32 accumulation and an fp32 output
+                         transform on top of what the emulation rounds)
+"""
+import sys
+from fractions import Fraction as Fr
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import conv
+from paper_2512_18453_amd import nova, synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def pts(pairs):
+    return [Fr(a, b) for a, b in pairs]
+
+
+def rel_l2(a, b):
+    return float(np.linalg.norm((a - b).ravel()) / max(np.linalg.norm(b.ravel()), 1e-300))
+
+
+def unblock(flat, n2, rows, chans):
+    """[n2][ceil(chans/32)][rows][32] flat device tensor -> numpy [n2][rows][chans] (fp64)."""
+    blocks = -(-chans // 32)
+    a = flat.detach().cpu().numpy().astype(np.float64).reshape(n2, blocks, rows, 32)
+    return a.transpose(0, 2, 1, 3).reshape(n2, rows, blocks * 32)[:, :, :chans]
+
+
+def run_stages(t, x, w, flags=0):
+    """All stages through the C ABI; returns numpy U, V, M (logical layouts) and y."""
+    N, C, H, W = x.shape
+    K = w.shape[0]
+    m, n2 = t.m, t.n * t.n
+    T = N * (-(-H // m)) * (-(-W // m))
+    xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+    U = nova.nova_filter_transform(t, wd)
+    V = nova.nova_input_transform(t, xd)
+    M = nova.nova_contract(t, U, V, N, C, H, W, K, flags)
+    y = nova.nova_output_transform(t, M, N, K, H, W, xd.dtype, flags)
+    y2 = nova.nova_winograd_conv2d(t, xd, U, K, flags=flags, images_per_slab=1)
+    torch.cuda.synchronize()
+    Kp = -(-K // 32) * 32
+    Ul = unblock(U, n2, Kp, C)
+    assert not Ul[:, K:, :].any()                       # padding rows are zero
+    out = dict(U=Ul[:, :K, :], V=unblock(V, n2, T, C), M=unblock(M, n2, T, K),
+               y=y.cpu().numpy().astype(np.float64), y_conv=y2.cpu().numpy().astype(np.float64))
+    return out
+
+
+SMALL_FP16 = [
+    # name, m, N, C, K, H, W
+    ("standard", 2, 2, 8, 8, 7, 9),
+    ("standard", 4, 2, 40, 48, 19, 14),
+    ("nova", 4, 3, 33, 70, 30, 41),
+    ("classic_half", 6, 2, 64, 32, 23, 56),
+    ("nova", 6, 2, 40, 130, 56, 56),
+    ("nova", 8, 3, 72, 96, 56, 56),
+    ("nova", 8, 1, 3, 5, 17, 70),
+]
+
+
+@pytest.mark.parametrize("name,m,N,C,K,H,W", SMALL_FP16)
+def test_fp16_stages_against_emulation(name, m, N, C, K, H, W):
+    say(f"[case] fp16 stages {name} F({m},3) N={N} C={C} K={K} H={H} W={W}")
+    points = synth.point_set(name, m)
+    x, w = synth.make_layer(N, C, K, H, W, seed=100 * m + C, dtype="f16")
+    t = nova.nova_make_transforms(points, m, 3)
+    got = run_stages(t, x, w)
+    x64, w64 = x.astype(np.float64), w.astype(np.float64)
+    y_o, U_o, V_o, M_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=16,
+                                                      want_intermediates=True)
+    assert np.array_equal(got["U"], U_o), "U differs"
+    assert np.array_equal(got["V"], V_o), "V differs"
+    assert rel_l2(got["M"], M_o) < 1e-5
+    assert np.array_equal(got["y"], got["y_conv"])
+    err = rel_l2(got["y"], y_o)
+    say(f"  rel-L2 vs emulation {err:.3e}; vs fp64 definition {rel_l2(got['y'], conv.direct_conv2d(x64, w64)):.3e}")
+    assert err < 5e-3
+
+
+def test_fp32_small_layer_against_definition():
+    cfg = synth.LAYER_CONFIGS["small_f43_fp32"]
+    say(f"[case] fp32 small layer {cfg}")
+    x, w = synth.make_layer(cfg["N"], cfg["C"], cfg["K"], cfg["H"], cfg["W"], seed=cfg["seed"],
+                            dtype="f32", x_dist=cfg["x_dist"])
+    points = synth.point_set("standard", 4)
+    t = nova.nova_make_transforms(points, 4, 3)
+    got = run_stages(t, x, w)
+    want = conv.direct_conv2d(x.astype(np.float64), w.astype(np.float64))
+    err, mx = rel_l2(got["y"], want), float(np.abs(got["y"] - want).max())
+    say(f"  rel-L2 {err:.3e} max-abs {mx:.3e}")
+    assert err <= 1e-5 and mx <= 1e-4
+    assert np.array_equal(got["y"], got["y_conv"])
+    _, U_o, V_o, _ = conv.winograd_conv2d_emulated(x.astype(np.float64), w.astype(np.float64), pts(points), 4,
+                                                   storage=32, want_intermediates=True)
+    assert np.array_equal(got["U"], U_o) and np.array_equal(got["V"], V_o)
+
+
+@pytest.mark.parametrize("name,m", [("nova", 4), ("nova", 6), ("classic_half", 6), ("nova", 8), ("standard", 8)])
+def test_fp32_other_tiles(name, m):
+    say(f"[case] fp32 {name} F({m},3)")
+    points = synth.point_set(name, m)
+    x, w = synth.make_layer(2, 40, 36, 3 * m + 2, 5 * m - 1, seed=7 + m, dtype="f32", x_dist="normal")
+    t = nova.nova_make_transforms(points, m, 3)
+    got = run_stages(t, x, w)
+    x64, w64 = x.astype(np.float64), w.astype(np.float64)
+    want = conv.direct_conv2d(x64, w64)
+    y_o, U_o, V_o, M_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=32, want_intermediates=True)
+    assert np.array_equal(got["U"], U_o) and np.array_equal(got["V"], V_o)
+    own = rel_l2(y_o, want)
+    err = rel_l2(got["y"], y_o)
+    say(f"  emulation vs definition {own:.3e}; gpu vs emulation {err:.3e}; gpu vs definition {rel_l2(got['y'], want):.3e}")
+    assert err <= max(1e-5, 4 * own)
+
+
+def test_generic_point_order_uses_the_same_contract():
+    # the same F(4,3) points in a non-canonical order run through the generic (non-paired) kernels
+    say("[case] generic path, permuted and asymmetric points")
+    for points in ([(1, 1), (0, 1), (-1, 1), (-2, 1), (2, 1)], [(1, 3), (0, 1), (-1, 1), (5, 4), (-2, 3)]):
+        t = nova.nova_make_transforms(points, 4, 3)
+        assert not t.symmetric
+        x, w = synth.make_layer(2, 20, 12, 11, 18, seed=3, dtype="f16")
+        got = run_stages(t, x, w)
+        y_o, U_o, V_o, M_o = conv.winograd_conv2d_emulated(x.astype(np.float64), w.astype(np.float64), pts(points), 4,
+                                                          storage=16, want_intermediates=True)
+        assert np.array_equal(got["U"], U_o) and np.array_equal(got["V"], V_o)
+        assert rel_l2(got["y"], y_o) < 5e-3
+
+
+def test_flags_relu_and_fp16_products():
+    say("[case] flags: relu, fp16 M")
+    points = synth.point_set("nova", 6)
+    x, w = synth.make_layer(2, 48, 40, 20, 31, seed=21, dtype="f16", x_dist="normal")
+    t = nova.nova_make_transforms(points, 6, 3)
+    x64, w64 = x.astype(np.float64), w.astype(np.float64)
+    got = run_stages(t, x, w, flags=nova.NOVA_FLAG_RELU)
+    y_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), 6, storage=16, relu=True)
+    assert (got["y"] >= 0).all() and rel_l2(got["y"], y_o) < 5e-3
+    assert ((got["y"] == 0) == (y_o == 0)).mean() > 0.999
+    got = run_stages(t, x, w, flags=nova.NOVA_FLAG_M_F16)
+    y_o, _, _, M_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), 6, storage=16, m_storage=16,
+                                                  want_intermediates=True)
+    assert rel_l2(got["M"], M_o) < 2e-4          # fp32 vs fp64 accumulation flips few binary16 roundings
+    assert rel_l2(got["y"], y_o) < 5e-3
+
+
+def test_integer_point_f83_blows_up_identically():
+    say("[case] integer-point F(8,3) in fp16: non-finite agreement")
+    points = synth.point_set("standard", 8)
+    x, w = synth.make_layer(1, 32, 8, 24, 24, seed=5, dtype="f16")
+    t = nova.nova_make_transforms(points, 8, 3)
+    got = run_stages(t, x, w)
+    y_o, U_o, V_o, M_o = conv.winograd_conv2d_emulated(x.astype(np.float64), w.astype(np.float64), pts(points), 8,
+                                                      storage=16, want_intermediates=True)
+    assert np.array_equal(np.isinf(got["V"]), np.isinf(V_o))
+    assert np.array_equal(got["V"][np.isfinite(V_o)], V_o[np.isfinite(V_o)])
+    assert np.array_equal(got["U"], U_o)
+    assert (np.isfinite(got["M"]) == np.isfinite(M_o)).mean() > 0.999
+    bad_gpu, bad_o = ~np.isfinite(got["y"]), ~np.isfinite(y_o)
+    say(f"  non-finite outputs: gpu {bad_gpu.mean():.3f} oracle {bad_o.mean():.3f}")
+    assert bad_o.mean() > 0.9 and (bad_gpu == bad_o).mean() > 0.99
+
+
+def test_slabs_and_workspace_errors():
+    say("[case] slab loop and workspace checks")
+    points = synth.point_set("nova", 4)
+    x, w = synth.make_layer(5, 32, 32, 12, 12, seed=2, dtype="f16")
+    t = nova.nova_make_transforms(points, 4, 3)
+    xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+    U = nova.nova_filter_transform(t, wd)
+    ys = [nova.nova_winograd_conv2d(t, xd, U, 32, images_per_slab=s).cpu() for s in (1, 2, 5, 0)]
+    for y in ys[1:]:
+        assert torch.equal(ys[0], y)
+    one = nova.nova_conv2d_workspace_bytes(5, 32, 12, 12, 32, 4, nova.NOVA_F16, 0, 1)
+    small = torch.empty(one - 256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(nova.NovaError) as exc:
+        nova.nova_winograd_conv2d(t, xd, U, 32, workspace=small)
+    assert exc.value.code == -5
+    torch.cuda.synchronize()
+
+
+def test_relu_maxpool():
+    say("[case] relu + 2x2 max-pool")
+    rng = np.random.default_rng(4)
+    for dtype in (np.float16, np.float32):
+        a = rng.standard_normal((3, 5, 9, 14)).astype(dtype)
+        got = nova.nova_relu_maxpool2x2(torch.from_numpy(a).to(DEV)).cpu().numpy().astype(np.float64)
+        assert np.array_equal(got, conv.relu_maxpool2x2(a.astype(np.float64)))
+
+
+def test_mid_layer_full_size():
+    cfg = synth.LAYER_CONFIGS["mid_f63_fp16"]
+    x, w = synth.make_layer(cfg["N"], cfg["C"], cfg["K"], cfg["H"], cfg["W"], seed=cfg["seed"], dtype="f16")
+    x64, w64 = x.astype(np.float64), w.astype(np.float64)
+    want = conv.direct_conv2d(x64, w64)
+    xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+    for name in ("classic_half", "nova"):
+        say(f"[case] mid layer F(6,3) {name} full size {cfg}")
+        points = synth.point_set(name, 6)
+        t = nova.nova_make_transforms(points, 6, 3)
+        U = nova.nova_filter_transform(t, wd)
+        y = nova.nova_winograd_conv2d(t, xd, U, cfg["K"]).cpu().numpy().astype(np.float64)
+        y_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), 6, storage=16)
+        e_emu, e_def = rel_l2(y, y_o), rel_l2(y, want)
+        say(f"  rel-L2 vs emulation {e_emu:.3e}; vs fp64 definition {e_def:.3e}")
+        assert e_emu < 5e-3
+
+
+def test_vgg_conv3_full_size_sampled_images():
+    # the benchmark workload at full size, in the launch configuration bench.py times; the oracle
+    # evaluates whole sampled images (outputs of different images are independent)
+    cfg = synth.LAYER_CONFIGS["vgg_conv3_f83_fp16"]
+    x, w = synth.make_layer(cfg["N"], cfg["C"], cfg["K"], cfg["H"], cfg["W"], seed=cfg["seed"], dtype="f16")
+    xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+    sample = [0, 17, 31]
+    x64, w64 = x[sample].astype(np.float64), w.astype(np.float64)
+    want = conv.direct_conv2d(x64, w64)
+    for name in ("nova", "standard"):
+        say(f"[case] VGG conv3 F(8,3) {name} full size, images {sample}")
+        points = synth.point_set(name, 8)
+        t = nova.nova_make_transforms(points, 8, 3)
+        U = nova.nova_filter_transform(t, wd)
+        y = nova.nova_winograd_conv2d(t, xd, U, cfg["K"])
+        torch.cuda.synchronize()
+        y = y[sample].cpu().numpy().astype(np.float64)
+        y_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), 8, storage=16)
+        if name == "nova":
+            e_emu, e_def = rel_l2(y, y_o), rel_l2(y, want)
+            say(f"  rel-L2 vs emulation {e_emu:.3e}; vs fp64 definition {e_def:.3e}")
+            assert np.isfinite(y).all() and e_emu < 5e-3
+        else:
+            bad, bad_o = ~np.isfinite(y), ~np.isfinite(y_o)
+            say(f"  non-finite outputs: gpu {bad.mean():.3f} oracle {bad_o.mean():.3f}")
+            assert bad_o.mean() > 0.9 and (bad == bad_o).mean() > 0.99

@@ -1,0 +1,114 @@
+"""CPU-only checks of libnova's host side: the library loads, exports every symbol the header
+declares, and its exact Cook-Toom construction agrees entry by entry with the oracle's (two
+independent implementations of the same construction).  No device call is made here."""
+import ctypes
+import os
+import re
+from fractions import Fraction as Fr
+
+import numpy as np
+import pytest
+
+from oracle import cook_toom as ct
+from paper_2512_18453_amd import nova, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+ALL_SETS = [("standard", 2), ("standard", 4), ("standard", 6), ("standard", 8), ("nova", 4), ("nova", 6),
+            ("nova", 8), ("classic_half", 6), ("dyadic", 4)]
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "nova.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(nova_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(nova.EXPORTS), declared ^ set(nova.EXPORTS)
+    L = nova.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert "gfx950" in nova.nova_version()
+
+
+@pytest.mark.parametrize("name,m", ALL_SETS)
+def test_matrices_equal_oracle_exactly(name, m):
+    points = synth.point_set(name, m)
+    t = nova.nova_make_transforms(points, m, 3)
+    assert (t.m, t.r, t.n, t.symmetric) == (m, 3, m + 2, True)
+    A, BT, G = ct.cook_toom([Fr(a, b) for a, b in points], m, 3)
+    assert nova.nova_get_matrix(t, nova.NOVA_MATRIX_A) == A
+    assert nova.nova_get_matrix(t, nova.NOVA_MATRIX_BT) == BT
+    assert nova.nova_get_matrix(t, nova.NOVA_MATRIX_G) == G
+    for which, mat in [(nova.NOVA_MATRIX_A, A), (nova.NOVA_MATRIX_BT, BT), (nova.NOVA_MATRIX_G, G)]:
+        assert np.array_equal(np.array(nova.nova_get_matrix_f64(t, which)), ct.to_f64(mat))
+        assert np.array_equal(np.array(nova.nova_get_matrix_f32(t, which), dtype=np.float32), ct.to_f32(mat))
+
+
+def test_other_shapes_and_orders():
+    # r = 5 and unordered, non-symmetric points: accepted by the host construction
+    pts = [Fr(1, 3), Fr(-2), Fr(0), Fr(5, 7), Fr(1), Fr(-1, 2), Fr(3, 2)]
+    t = nova.nova_make_transforms(pts, 4, 5)
+    assert (t.n, t.symmetric) == (8, False)
+    A, BT, G = ct.cook_toom(pts, 4, 5)
+    assert nova.nova_get_matrix(t, nova.NOVA_MATRIX_BT) == BT and nova.nova_get_matrix(t, nova.NOVA_MATRIX_G) == G
+    # symmetric set in a non-canonical order is not flagged symmetric
+    t2 = nova.nova_make_transforms([1, -1, 0, 2, -2], 4, 3)
+    assert not t2.symmetric
+    assert nova.nova_get_matrix(t2, nova.NOVA_MATRIX_A) == ct.cook_toom([1, -1, 0, 2, -2], 4, 3)[0]
+
+
+@pytest.mark.parametrize("name,m", ALL_SETS)
+def test_kappa_matches_oracle(name, m):
+    points = [Fr(a, b) for a, b in synth.point_set(name, m)]
+    t = nova.nova_make_transforms(points, m, 3)
+    got = nova.nova_kappa(t)
+    A, BT, G = ct.cook_toom(points, m, 3)
+    want = dict(V=ct.kappa_V(points), A=ct.kappa(A), B=ct.kappa(BT), G=ct.kappa(G))
+    for key in want:
+        assert got[key] == pytest.approx(want[key], rel=1e-7), key
+
+
+def test_error_codes():
+    L = nova.lib()
+    handle = ctypes.c_void_p()
+
+    def make(pairs, m, r=3, n_points=None):
+        arr = (nova.nova_rational * max(len(pairs), 1))()
+        for i, (a, b) in enumerate(pairs):
+            arr[i].num, arr[i].den = a, b
+        return L.nova_make_transforms(arr, len(pairs) if n_points is None else n_points, m, r, ctypes.byref(handle))
+
+    std4 = synth.STANDARD[4]
+    assert make(std4, 4) == 0
+    L.nova_free_transforms(handle)
+    assert make(std4[:-1], 4) == -1                         # wrong count
+    assert make(std4, 0) == -1 and make(std4, 4, 0) == -1   # bad m / r
+    assert make([(0, 1), (1, 0), (-1, 1), (2, 1), (-2, 1)], 4) == -1      # zero denominator
+    assert make([(0, 1), (1, 1), (2, 2), (2, 1), (-2, 1)], 4) == -2       # 1 == 2/2
+    assert handle.value is None
+    big = [(0, 1)] + [(s * (10 ** 9 + 7 * i), 10 ** 9 + 9 + i) for i in range(4) for s in (1, -1)]
+    assert make(big, 8) == -3                               # exact entries exceed 64 bits
+    assert L.nova_make_transforms(None, 5, 4, 3, ctypes.byref(handle)) == -1
+    assert make([(i, 1) for i in range(20)], 18, 3) == -1   # n > 16
+    assert L.nova_get_matrix(None, 0, None) == -1
+    assert L.nova_strerror(-2).decode().startswith("duplicate")
+    # device entry points reject bad arguments before touching the GPU
+    t = nova.nova_make_transforms(synth.STANDARD[4], 4, 3)
+    assert L.nova_winograd_conv2d(t.handle, None, None, None, 1, 1, 1, 1, 1, 0, 0, None, 0, None) == -1
+    t5 = nova.nova_make_transforms([0, 1, -1, 2, -2, 3, -3], 4, 5)
+    assert L.nova_filter_transform(t5.handle, 1, 1, 1, 0, 1, None) == -6      # r = 5: host only
+    assert L.nova_conv2d_workspace_bytes(1, 1, 1, 1, 1, 5, 0, 0, 0) == 0
+
+
+def test_sizes_follow_documented_layouts():
+    # U [n*n][ceil(C/32)][Kp][32], V [n*n][ceil(C/32)][T][32], M [n*n][ceil(K/32)][T][32]
+    assert nova.nova_filter_bytes(256, 256, 8, nova.NOVA_F16) == 100 * 8 * 256 * 32 * 2
+    assert nova.nova_filter_bytes(20, 3, 4, nova.NOVA_F32) == 36 * 1 * 32 * 32 * 4
+    assert nova.nova_input_bytes(32, 256, 56, 56, 8, nova.NOVA_F16) == 100 * 8 * (32 * 49) * 32 * 2
+    assert nova.nova_product_bytes(2, 40, 9, 13, 6, nova.NOVA_F16) == 64 * 2 * (2 * 2 * 3) * 32 * 4
+    assert nova.nova_product_bytes(2, 40, 9, 13, 6, nova.NOVA_F16, nova.NOVA_FLAG_M_F16) == 64 * 2 * 12 * 32 * 2
+    whole = nova.nova_conv2d_workspace_bytes(32, 256, 56, 56, 256, 8, nova.NOVA_F16, 0, 32)
+    assert whole == 100 * 8 * 1568 * 32 * 2 + 100 * 8 * 1568 * 32 * 4
+    one = nova.nova_conv2d_workspace_bytes(32, 256, 56, 56, 256, 8, nova.NOVA_F16, 0, 1)
+    assert one * 32 == whole
+    default = nova.nova_conv2d_workspace_bytes(32, 256, 56, 56, 256, 8, nova.NOVA_F16, 0, 0)
+    assert one <= default <= whole and default % one == 0
