@@ -16,6 +16,17 @@ __device__ __forceinline__ float load_f32(const f16 *p) { return (float)*p; }
 __device__ __forceinline__ void store_from_f32(float *p, float v) { *p = v; }
 __device__ __forceinline__ void store_from_f32(f16 *p, float v) { *p = (f16)v; }
 
+// binary32 -> storage as its own rounding step.  Without the barrier the compiler merges a
+// fused multiply-add and the conversion into one v_fma_mixlo_f16, which rounds the exact
+// a*b+c once to binary16 and therefore disagrees, in the last place, with "round to binary32,
+// then to binary16" -- the order the input-transform contract prescribes.
+__device__ __forceinline__ void store_rounded_twice(float *p, float v) { *p = v; }
+__device__ __forceinline__ void store_rounded_twice(f16 *p, float v)
+{
+    asm volatile("" : "+v"(v));
+    *p = (f16)v;
+}
+
 __device__ __forceinline__ float fma32(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
 
 // binary64 -> storage with a single rounding.  For binary16 the value first goes to binary32

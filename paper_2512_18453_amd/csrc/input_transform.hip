@@ -122,7 +122,7 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
         float o[N];
         input_transform_1d<N, SYM>(tmp[i], o, coef);
 #pragma unroll
-        for (int jj = 0; jj < N; ++jj) store_from_f32(dst + (size_t)(i * N + jj) * xi_stride, o[jj]);
+        for (int jj = 0; jj < N; ++jj) store_rounded_twice(dst + (size_t)(i * N + jj) * xi_stride, o[jj]);
     }
 }
 

@@ -38,6 +38,18 @@ def rel_l2(a, b):
     return float(np.linalg.norm((a - b).ravel()) / max(np.linalg.norm(b.ravel()), 1e-300))
 
 
+def same(got, want, what):
+    """Bit-for-bit comparison with a readable failure."""
+    if np.array_equal(got, want, equal_nan=True):
+        return
+    bad = np.argwhere(~((got == want) | (np.isnan(got) & np.isnan(want))))
+    lines = [f"{what}: {len(bad)} of {got.size} entries differ; first:"]
+    for idx in bad[:12]:
+        idx = tuple(idx)
+        lines.append(f"  {idx}: gpu {got[idx]!r} oracle {want[idx]!r}")
+    raise AssertionError("\n".join(lines))
+
+
 def unblock(flat, n2, rows, chans):
     """[n2][ceil(chans/32)][rows][32] flat device tensor -> numpy [n2][rows][chans] (fp64)."""
     blocks = -(-chans // 32)
@@ -88,8 +100,8 @@ def test_fp16_stages_against_emulation(name, m, N, C, K, H, W):
     x64, w64 = x.astype(np.float64), w.astype(np.float64)
     y_o, U_o, V_o, M_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=16,
                                                       want_intermediates=True)
-    assert np.array_equal(got["U"], U_o), "U differs"
-    assert np.array_equal(got["V"], V_o), "V differs"
+    same(got["U"], U_o, "U")
+    same(got["V"], V_o, "V")
     assert rel_l2(got["M"], M_o) < 1e-5
     assert np.array_equal(got["y"], got["y_conv"])
     err = rel_l2(got["y"], y_o)
@@ -112,7 +124,8 @@ def test_fp32_small_layer_against_definition():
     assert np.array_equal(got["y"], got["y_conv"])
     _, U_o, V_o, _ = conv.winograd_conv2d_emulated(x.astype(np.float64), w.astype(np.float64), pts(points), 4,
                                                    storage=32, want_intermediates=True)
-    assert np.array_equal(got["U"], U_o) and np.array_equal(got["V"], V_o)
+    same(got["U"], U_o, "U")
+    same(got["V"], V_o, "V")
 
 
 @pytest.mark.parametrize("name,m", [("nova", 4), ("nova", 6), ("classic_half", 6), ("nova", 8), ("standard", 8)])
@@ -125,7 +138,8 @@ def test_fp32_other_tiles(name, m):
     x64, w64 = x.astype(np.float64), w.astype(np.float64)
     want = conv.direct_conv2d(x64, w64)
     y_o, U_o, V_o, M_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=32, want_intermediates=True)
-    assert np.array_equal(got["U"], U_o) and np.array_equal(got["V"], V_o)
+    same(got["U"], U_o, "U")
+    same(got["V"], V_o, "V")
     own = rel_l2(y_o, want)
     err = rel_l2(got["y"], y_o)
     say(f"  emulation vs definition {own:.3e}; gpu vs emulation {err:.3e}; gpu vs definition {rel_l2(got['y'], want):.3e}")
@@ -142,7 +156,8 @@ def test_generic_point_order_uses_the_same_contract():
         got = run_stages(t, x, w)
         y_o, U_o, V_o, M_o = conv.winograd_conv2d_emulated(x.astype(np.float64), w.astype(np.float64), pts(points), 4,
                                                           storage=16, want_intermediates=True)
-        assert np.array_equal(got["U"], U_o) and np.array_equal(got["V"], V_o)
+        same(got["U"], U_o, "U")
+        same(got["V"], V_o, "V")
         assert rel_l2(got["y"], y_o) < 5e-3
 
 
