@@ -2,10 +2,11 @@
 // zero-padded image, x [N][C][H][W] -> V [n*n][C/32][T][32].
 //
 // One workgroup takes one image, one tile row, a group of TWB neighbouring tiles and one block
-// of 32 channels.  The (n rows) x (TWB*m + 2 columns) x 32-channel input strip is staged in LDS
-// with the channel index fastest, so that global reads run along W and the per-thread tile reads
-// (thread = one tile x one channel, 32 consecutive lanes = 32 consecutive channels) hit 32
-// different LDS words.  Each thread then transforms its tile in registers and writes n*n values,
+// of 32 channels.  The 32-channel x (n rows) x (TWB*m + 2 columns) input strip is staged in LDS
+// in the order it has in memory (16-byte pieces when W allows, all loads of a round in flight
+// together), with a channel pitch that puts the 32 channels of a half-wave into 32 different
+// banks for the per-thread tile reads (thread = one tile x one channel, 32 consecutive lanes =
+// 32 consecutive channels).  Each thread then transforms its tile in registers and writes n*n values,
 // 64 (fp16) or 128 (fp32) contiguous bytes per half-wave and position xi; the TWB tiles of the
 // group are adjacent in t, so a workgroup writes TWB*64 contiguous bytes per xi.
 //
@@ -54,61 +55,112 @@ __device__ __forceinline__ void input_transform_1d(const float (&v)[N], float (&
     }
 }
 
-template <typename T> struct LdsPitch;
-template <> struct LdsPitch<f16> { static constexpr int value = kChanBlock + 2; };   // 17 words: odd
-template <> struct LdsPitch<float> { static constexpr int value = kChanBlock + 1; }; // 33 words: odd
+// LDS strip: [32 channels][N rows][row_pitch columns], columns fastest (the order of x in
+// memory, so staging moves 16-byte pieces); strip column lc holds image column w_al + lc, where
+// w_al is the first needed column w_lo rounded down to a whole piece.  The channel pitch is
+// 4 * odd elements: rows stay 8-byte aligned for the staging writes, and the 32 channels that a
+// half-wave reads at one (row, column) fall into 32 different banks.
+struct StripShape {
+    int twb;         // tiles per group
+    int groups;      // tile groups per tile row
+    int pieces;      // 16-byte pieces per strip row (vector path) / columns per row (scalar path)
+    int row_pitch;   // elements
+    int ch_pitch;    // elements
+    unsigned piece_magic;   // ceil(2^32 / pieces): s / pieces == mulhi(s, magic) while s * pieces < 2^32
+};
 
-template <int N, typename T, bool SYM>
+template <int N, typename T, bool SYM, bool VEC>
 __global__ void __launch_bounds__(512)
 input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H, int W,
-                       int tiles_h, int tiles_w, int twb, int groups, int c_blocks, long long Ttot,
+                       int tiles_h, int tiles_w, int c_blocks, long long Ttot, StripShape sh,
                        InCoef<N> coef)
 {
     constexpr int M = N - 2;
-    constexpr int CP = LdsPitch<T>::value;
+    constexpr int PE = 16 / (int)sizeof(T);      // elements per 16-byte piece
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
     extern __shared__ __align__(16) unsigned char lds_raw[];
     T *lds = reinterpret_cast<T *>(lds_raw);
 
     // block -> (image, channel block, tile row, tile group); group fastest
     unsigned bid = xcd_local_block_id(blockIdx.x, gridDim.x);
-    const int tg = bid % groups; bid /= groups;
+    const int tg = bid % sh.groups; bid /= sh.groups;
     const int tr = bid % tiles_h; bid /= tiles_h;
     const int cb = bid % c_blocks; bid /= c_blocks;
     const int img = bid;
 
-    const int tc0 = tg * twb;
-    const int cols = twb * M + 2;
+    const int tc0 = tg * sh.twb;
     const int h_lo = tr * M - 1;          // image row of strip row 0
-    const int w_lo = tc0 * M - 1;         // image column of strip column 0
+    const int w_lo = tc0 * M - 1;         // first image column the group needs
+    int w_al = w_lo;                      // image column of strip column 0
 
-    // ---- stage the strip: one (channel, row) line per wave iteration, lanes along W
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int n_waves = (blockDim.x + 63) >> 6;
-    for (int line = wave; line < kChanBlock * N; line += n_waves) {
-        const int c_in = line / N, a = line - c_in * N;
-        const int c = cb * kChanBlock + c_in;
-        const int h = h_lo + a;
-        const bool row_ok = c < C && h >= 0 && h < H;
-        const T *src = x + (((size_t)img * C + (row_ok ? c : 0)) * H + (row_ok ? h : 0)) * W;
-        for (int col = lane; col < cols; col += 64) {
-            const int w = w_lo + col;
-            T val = (T)0.0f;
-            if (row_ok && w >= 0 && w < W) val = src[w];
-            lds[(a * cols + col) * CP + c_in] = val;
+    if constexpr (VEC) {
+        // W is a multiple of PE and x is 16-byte aligned: every piece is wholly inside or outside
+        // the image.  All loads of a round are issued before the first LDS write waits on them.
+        w_al = (w_lo + PE) / PE * PE - PE;        // floor to a multiple of PE (w_lo >= -1)
+        const int slots = kChanBlock * N * sh.pieces;
+        constexpr int R = 4;
+        for (int base = threadIdx.x; base < slots; base += R * (int)blockDim.x) {
+            u32x4 val[R];
+            int dst[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int s = base + r * (int)blockDim.x;
+                const int line = (int)__umulhi((unsigned)s, sh.piece_magic);
+                const int q = s - line * sh.pieces;
+                const int c_in = line / N, a = line - c_in * N;
+                const int c = cb * kChanBlock + c_in, h = h_lo + a, w = w_al + q * PE;
+                const bool ok = s < slots && c < C && h >= 0 && h < H && w >= 0 && w < W;
+                dst[r] = s < slots ? c_in * sh.ch_pitch + a * sh.row_pitch + q * PE : -1;
+                val[r] = u32x4{0u, 0u, 0u, 0u};
+                if (ok) val[r] = *reinterpret_cast<const u32x4 *>(x + (((size_t)img * C + c) * H + h) * W + w);
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (dst[r] >= 0) {
+                    u32x2 *p = reinterpret_cast<u32x2 *>(lds + dst[r]);
+                    p[0] = u32x2{val[r].x, val[r].y};
+                    p[1] = u32x2{val[r].z, val[r].w};
+                }
+        }
+    } else {
+        // any W: element-wise, lanes along W
+        const int cols = sh.pieces;
+        const int slots = kChanBlock * N * cols;
+        constexpr int R = 8;
+        for (int base = threadIdx.x; base < slots; base += R * (int)blockDim.x) {
+            T val[R];
+            int dst[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int s = base + r * (int)blockDim.x;
+                const int line = (int)__umulhi((unsigned)s, sh.piece_magic);
+                const int q = s - line * cols;
+                const int c_in = line / N, a = line - c_in * N;
+                const int c = cb * kChanBlock + c_in, h = h_lo + a, w = w_al + q;
+                const bool ok = s < slots && c < C && h >= 0 && h < H && w >= 0 && w < W;
+                dst[r] = s < slots ? c_in * sh.ch_pitch + a * sh.row_pitch + q : -1;
+                val[r] = (T)0.0f;
+                if (ok) val[r] = x[(((size_t)img * C + c) * H + h) * W + w];
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (dst[r] >= 0) lds[dst[r]] = val[r];
         }
     }
     __syncthreads();
 
     // ---- transform: thread = (tile j of the group, channel c_in)
     const int j = threadIdx.x >> 5, c_in = threadIdx.x & 31;
-    if (j >= twb || tc0 + j >= tiles_w) return;
+    if (j >= sh.twb || tc0 + j >= tiles_w) return;
 
+    const T *tile = lds + c_in * sh.ch_pitch + (w_lo - w_al) + j * M;
     float tmp[N][N];
 #pragma unroll
     for (int b = 0; b < N; ++b) {
         float d[N], o[N];
 #pragma unroll
-        for (int a = 0; a < N; ++a) d[a] = load_f32(&lds[(a * cols + j * M + b) * CP + c_in]);
+        for (int a = 0; a < N; ++a) d[a] = load_f32(tile + a * sh.row_pitch + b);
         input_transform_1d<N, SYM>(d, o, coef);
 #pragma unroll
         for (int i = 0; i < N; ++i) tmp[i][b] = o[i];
@@ -142,27 +194,52 @@ static void fill_in_coef(const nova_transforms *t, InCoef<N> &k)
         }
 }
 
+// Strip geometry for `twb` tiles per group; returns the LDS bytes it needs.
+template <int N, typename T>
+static size_t strip_shape(int twb, bool vec, StripShape &sh)
+{
+    constexpr int M = N - 2;
+    constexpr int PE = 16 / (int)sizeof(T);
+    const int need = twb * M + 2;                       // columns w_lo .. w_lo + need - 1
+    if (vec) {
+        // worst-case offset of w_lo inside its piece is PE - 1
+        sh.pieces = (need + PE - 1 + PE - 1) / PE;
+        sh.row_pitch = sh.pieces * PE;
+    } else {
+        sh.pieces = need;
+        sh.row_pitch = (need + 3) / 4 * 4;
+    }
+    int chp = N * sh.row_pitch;                         // multiple of 4
+    if ((chp / 4) % 2 == 0) chp += 4;                   // 4 * odd
+    sh.ch_pitch = chp;
+    sh.twb = twb;
+    sh.piece_magic = (unsigned)((((unsigned long long)1 << 32) + sh.pieces - 1) / sh.pieces);
+    return (size_t)kChanBlock * chp * sizeof(T);
+}
+
 template <int N, typename T>
 static int launch_it(const nova_transforms *t, const void *x, void *V, const Geometry &g, hipStream_t stream)
 {
-    constexpr int M = N - 2;
-    constexpr int CP = LdsPitch<T>::value;
+    constexpr int PE = 16 / (int)sizeof(T);
     InCoef<N> coef;
     fill_in_coef<N>(t, coef);
+    const bool vec = g.W % PE == 0 && ((uintptr_t)x % 16) == 0;
     // tiles per group: at most 16 (512 threads) and an LDS strip of at most 64 KiB
-    const int lds_budget = 64 * 1024;
-    int twb_max = (lds_budget / (int)(N * CP * sizeof(T)) - 2) / M;
-    twb_max = twb_max > 16 ? 16 : (twb_max < 1 ? 1 : twb_max);
-    const int groups = ceil_div(g.tiles_w, twb_max);
-    const int twb = ceil_div(g.tiles_w, groups);
-    const size_t lds_bytes = (size_t)N * (twb * M + 2) * CP * sizeof(T);
+    StripShape sh;
+    int twb_max = 16;
+    while (twb_max > 1 && strip_shape<N, T>(twb_max, vec, sh) > 64 * 1024) --twb_max;
+    sh.groups = ceil_div(g.tiles_w, twb_max);
+    const int twb = ceil_div(g.tiles_w, sh.groups);
+    const size_t lds_bytes = strip_shape<N, T>(twb, vec, sh);
+    if (lds_bytes > 64 * 1024 || sh.pieces < 2) return (int)hipErrorInvalidValue;
     const int threads = ((twb * 32 + 63) / 64) * 64;
-    const long long blocks = (long long)groups * g.tiles_h * g.c_blocks * g.N;
+    const long long blocks = (long long)sh.groups * g.tiles_h * g.c_blocks * g.N;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
-    auto kern = t->symmetric ? input_transform_kernel<N, T, true> : input_transform_kernel<N, T, false>;
+    void (*kern)(const T *, T *, int, int, int, int, int, int, long long, StripShape, InCoef<N>);
+    if (t->symmetric) kern = vec ? input_transform_kernel<N, T, true, true> : input_transform_kernel<N, T, true, false>;
+    else              kern = vec ? input_transform_kernel<N, T, false, true> : input_transform_kernel<N, T, false, false>;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds_bytes, stream,
-                       (const T *)x, (T *)V, g.C, g.H, g.W, g.tiles_h, g.tiles_w, twb, groups,
-                       g.c_blocks, g.T, coef);
+                       (const T *)x, (T *)V, g.C, g.H, g.W, g.tiles_h, g.tiles_w, g.c_blocks, g.T, sh, coef);
     return (int)hipGetLastError();
 }
 
