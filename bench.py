@@ -84,41 +84,43 @@ def main():
     direct_flop = 2.0 * N * K * C * H * W * 9
     value = direct_flop / (ms_per_step * 1e-3) / 1e12
 
-    # ---- per-stage timing in the same launch configuration (one launch = one slab)
+    # ---- per-stage timing inside the pipeline, same launch configuration (one launch = one slab):
+    # the three stage entry points are called in sequence, as nova_winograd_conv2d does, with an
+    # event between them, so each kernel sees the cache state it sees in the timed region above
     tiles = -(-H // m) * (-(-W // m))
     T_slab = slab_imgs * tiles
-    xs = xd[:slab_imgs].contiguous()
-    V = nova.nova_input_transform(t, xs)
-    M = nova.nova_contract(t, U, V, slab_imgs, C, H, W, K, flags)
-    ys = nova.nova_output_transform(t, M, slab_imgs, K, H, W, tdtype, flags)
-
-    def time_stage(fn, reps):
-        for _ in range(3):
-            fn()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(reps):
-            fn()
-        b.record()
-        torch.cuda.synchronize()
-        return a.elapsed_time(b) / reps * 1e-3
-
-    reps = max(10, args.steps)
     cb, kb = -(-C // 32) * 32, -(-K // 32) * 32
+    V = torch.empty(n * n * T_slab * cb, dtype=tdtype, device=dev)
+    M = torch.empty(n * n * T_slab * kb, dtype=torch.float16 if m_es == 2 else torch.float32, device=dev)
+    slabs = [(i, min(slab_imgs, N - i)) for i in range(0, N, slab_imgs)]
+    reps = max(10, args.steps)
+    marks = []
+    for rep in range(reps + 3):
+        for (i0, cnt) in slabs:
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            ev[0].record()
+            nova.nova_input_transform(t, xd[i0:i0 + cnt], V=V)
+            ev[1].record()
+            nova.nova_contract(t, U, V, cnt, C, H, W, K, flags, M=M)
+            ev[2].record()
+            nova.nova_output_transform(t, M, cnt, K, H, W, tdtype, flags, y=y[i0:i0 + cnt])
+            ev[3].record()
+            if rep >= 3 and cnt == slab_imgs:
+                marks.append(ev)
+    torch.cuda.synchronize()
+    s_in, s_c, s_out = [sum(e[i].elapsed_time(e[i + 1]) for e in marks) / len(marks) * 1e-3 for i in range(3)]
     x_b = slab_imgs * C * H * W * es
     y_b = slab_imgs * K * H * W * es
     V_b = n * n * T_slab * cb * es
     M_b = n * n * T_slab * kb * m_es
     U_b = n * n * kb * cb * es
-    stages = {}
-    s_in = time_stage(lambda: nova.nova_input_transform(t, xs, V=V), reps)
-    stages["input_transform"] = dict(us=s_in * 1e6, bytes=x_b + V_b, gbs=(x_b + V_b) / s_in / 1e9)
-    s_c = time_stage(lambda: nova.nova_contract(t, U, V, slab_imgs, C, H, W, K, flags, M=M), reps)
     gemm_flop = 2.0 * n * n * T_slab * C * K
-    stages["contract"] = dict(us=s_c * 1e6, bytes=U_b + V_b + M_b, gbs=(U_b + V_b + M_b) / s_c / 1e9,
-                              tflops=gemm_flop / s_c / 1e12, mfma_frac=gemm_flop / s_c / 1e12 / MFMA_F16_PEAK_TFLOPS)
-    s_out = time_stage(lambda: nova.nova_output_transform(t, M, slab_imgs, K, H, W, tdtype, flags, y=ys), reps)
-    stages["output_transform"] = dict(us=s_out * 1e6, bytes=M_b + y_b, gbs=(M_b + y_b) / s_out / 1e9)
+    stages = {
+        "input_transform": dict(us=s_in * 1e6, bytes=x_b + V_b, gbs=(x_b + V_b) / s_in / 1e9),
+        "contract": dict(us=s_c * 1e6, bytes=U_b + V_b + M_b, gbs=(U_b + V_b + M_b) / s_c / 1e9,
+                         tflops=gemm_flop / s_c / 1e12, mfma_frac=gemm_flop / s_c / 1e12 / MFMA_F16_PEAK_TFLOPS),
+        "output_transform": dict(us=s_out * 1e6, bytes=M_b + y_b, gbs=(M_b + y_b) / s_out / 1e9),
+    }
     for st in stages.values():
         st["hbm_frac"] = st["gbs"] / HBM_PEAK_GBS
     dominant = max(stages, key=lambda k: stages[k]["us"])

@@ -44,7 +44,7 @@ static size_t m_bytes(const Geometry &g, int dtype, int flags)
     return (size_t)g.n * g.n * g.k_blocks * (size_t)g.T * kChanBlock * es;
 }
 
-constexpr size_t kDefaultSlabBytes = (size_t)64 << 20;
+constexpr size_t kDefaultSlabBytes = (size_t)2 << 30;
 
 }  // namespace nova
 

@@ -47,25 +47,35 @@ __device__ __forceinline__ void output_transform_1d(const float (&v)[N], float (
     }
 }
 
-template <int N, typename T, typename MT, bool SYM>
+struct OutShape {
+    int twb;          // tiles per group
+    int groups;       // tile groups per tile row
+    int cols_pitch;   // LDS elements per output row of the group
+    int k_pitch;      // LDS elements per channel
+};
+
+template <int N, typename T, typename MT, bool SYM, bool VEC>
 __global__ void __launch_bounds__(512)
 output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int H, int W,
-                        int tiles_h, int tiles_w, int twb, int groups, int k_blocks, long long Ttot,
-                        int cols_pitch, int k_pitch, int relu, OutCoef<N> coef)
+                        int tiles_h, int tiles_w, int k_blocks, long long Ttot, OutShape sh, int relu,
+                        OutCoef<N> coef)
 {
     constexpr int M = N - 2;
+    constexpr int PE = 16 / (int)sizeof(T);
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
     extern __shared__ __align__(16) unsigned char lds_raw[];
     T *lds = reinterpret_cast<T *>(lds_raw);
 
     unsigned bid = xcd_local_block_id(blockIdx.x, gridDim.x);
-    const int tg = bid % groups; bid /= groups;
+    const int tg = bid % sh.groups; bid /= sh.groups;
     const int tr = bid % tiles_h; bid /= tiles_h;
     const int kb = bid % k_blocks; bid /= k_blocks;
     const int img = bid;
-    const int tc0 = tg * twb;
+    const int tc0 = tg * sh.twb;
 
     const int j = threadIdx.x >> 5, k_in = threadIdx.x & 31;
-    if (j < twb && tc0 + j < tiles_w) {
+    if (j < sh.twb && tc0 + j < tiles_w) {
         const long long t = ((long long)img * tiles_h + tr) * tiles_w + tc0 + j;
         const size_t xi_stride = (size_t)k_blocks * Ttot * kChanBlock;
         const MT *src = Mp + ((size_t)kb * Ttot + t) * kChanBlock + k_in;
@@ -80,7 +90,7 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
 #pragma unroll
             for (int p = 0; p < M; ++p) z[p][b] = o[p];
         }
-        T *dst = lds + k_in * k_pitch + j * M;
+        T *dst = lds + k_in * sh.k_pitch + j * M;
 #pragma unroll
         for (int p = 0; p < M; ++p) {
             float o[M];
@@ -89,26 +99,43 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
             for (int q = 0; q < M; ++q) {
                 float val = o[q];
                 if (relu) val = val < 0.0f ? 0.0f : val;      // NaN stays NaN
-                store_from_f32(dst + p * cols_pitch + q, val);
+                store_from_f32(dst + p * sh.cols_pitch + q, val);
             }
         }
     }
     __syncthreads();
 
-    // ---- store: one (channel, row) line per wave iteration, lanes along W
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int n_waves = (blockDim.x + 63) >> 6;
+    // ---- store the [32 channels][m rows][columns] block, lanes along W
     const int w0 = tc0 * M;
-    int cols = twb * M;
+    int cols = sh.twb * M;
     if (w0 + cols > W) cols = W - w0;
-    for (int line = wave; line < kChanBlock * M; line += n_waves) {
-        const int kk = line / M, p = line - kk * M;
-        const int k = kb * kChanBlock + kk;
-        const int h = tr * M + p;
-        if (k >= K || h >= H) continue;
-        T *out = y + (((size_t)img * K + k) * H + h) * W + w0;
-        const T *in = lds + kk * k_pitch + p * cols_pitch;
-        for (int col = lane; col < cols; col += 64) out[col] = in[col];
+    if constexpr (VEC) {
+        // W, w0 and cols are multiples of PE and y is 16-byte aligned
+        const int pieces = cols / PE;
+        const unsigned magic = (unsigned)((((unsigned long long)1 << 32) + pieces - 1) / pieces);
+        const int slots = kChanBlock * M * pieces;
+        for (int s = threadIdx.x; s < slots; s += (int)blockDim.x) {
+            const int line = pieces > 1 ? (int)__umulhi((unsigned)s, magic) : s;
+            const int q = s - line * pieces;
+            const int kk = line / M, p = line - kk * M;
+            const int k = kb * kChanBlock + kk, h = tr * M + p;
+            if (k >= K || h >= H) continue;
+            const u32x2 *in = reinterpret_cast<const u32x2 *>(lds + kk * sh.k_pitch + p * sh.cols_pitch + q * PE);
+            const u32x2 lo = in[0], hi = in[1];
+            *reinterpret_cast<u32x4 *>(y + (((size_t)img * K + k) * H + h) * W + w0 + q * PE) =
+                u32x4{lo.x, lo.y, hi.x, hi.y};
+        }
+    } else {
+        const unsigned magic = (unsigned)((((unsigned long long)1 << 32) + cols - 1) / cols);
+        const int slots = kChanBlock * M * cols;
+        for (int s = threadIdx.x; s < slots; s += (int)blockDim.x) {
+            const int line = cols > 1 ? (int)__umulhi((unsigned)s, magic) : s;
+            const int q = s - line * cols;
+            const int kk = line / M, p = line - kk * M;
+            const int k = kb * kChanBlock + kk, h = tr * M + p;
+            if (k >= K || h >= H) continue;
+            y[(((size_t)img * K + k) * H + h) * W + w0 + q] = lds[kk * sh.k_pitch + p * sh.cols_pitch + q];
+        }
     }
 }
 
@@ -121,32 +148,45 @@ static void fill_out_coef(const nova_transforms *t, OutCoef<N> &k)
         for (int i = 0; i < M; ++i) k.pw[j * M + i] = t->A32[(2 * j + 1) * M + i];
 }
 
+template <int N, typename T>
+static size_t out_shape(int twb, OutShape &sh)
+{
+    constexpr int M = N - 2;
+    sh.twb = twb;
+    sh.cols_pitch = (twb * M + 3) / 4 * 4;              // rows stay 8-byte aligned
+    int kp = M * sh.cols_pitch;                         // multiple of 4
+    // channel pitch 4 * odd elements: 8-byte aligned rows, and the 32 channels of a half-wave
+    // writing one (row, column) fall into different banks
+    if ((kp / 4) % 2 == 0) kp += 4;
+    sh.k_pitch = kp;
+    return (size_t)kChanBlock * kp * sizeof(T);
+}
+
 template <int N, typename T, typename MT>
 static int launch_ot(const nova_transforms *t, const void *Mp, void *y, const Geometry &g, int flags,
                      hipStream_t stream)
 {
     constexpr int M = N - 2;
+    constexpr int PE = 16 / (int)sizeof(T);
     OutCoef<N> coef;
     fill_out_coef<N>(t, coef);
-    const int lds_budget = 64 * 1024;
-    int twb_max = (lds_budget / (int)(kChanBlock * M * sizeof(T)) - 4) / M;
-    twb_max = twb_max > 16 ? 16 : (twb_max < 1 ? 1 : twb_max);
-    const int groups = ceil_div(g.tiles_w, twb_max);
-    const int twb = ceil_div(g.tiles_w, groups);
-    const int cols_pitch = twb * M;
-    // per-channel pitch: an odd number of 32-bit words, so that the 32 channels of a half-wave
-    // land in different banks when they write the same (row, column)
-    int k_pitch = M * cols_pitch;
-    if (sizeof(T) == 2) { while ((k_pitch % 2) != 0 || ((k_pitch / 2) % 2) == 0) ++k_pitch; }
-    else                { while ((k_pitch % 2) == 0) ++k_pitch; }
-    const size_t lds_bytes = (size_t)kChanBlock * k_pitch * sizeof(T);
+    OutShape sh;
+    int twb_max = 16;
+    while (twb_max > 1 && out_shape<N, T>(twb_max, sh) > 64 * 1024) --twb_max;
+    sh.groups = ceil_div(g.tiles_w, twb_max);
+    const int twb = ceil_div(g.tiles_w, sh.groups);
+    const size_t lds_bytes = out_shape<N, T>(twb, sh);
+    if (lds_bytes > 64 * 1024) return (int)hipErrorInvalidValue;
+    const bool vec = g.W % PE == 0 && ((uintptr_t)y % 16) == 0 && (sh.groups == 1 || (twb * M) % PE == 0);
     const int threads = ((twb * 32 + 63) / 64) * 64;
-    const long long blocks = (long long)groups * g.tiles_h * g.k_blocks * g.N;
+    const long long blocks = (long long)sh.groups * g.tiles_h * g.k_blocks * g.N;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
-    auto kern = t->symmetric ? output_transform_kernel<N, T, MT, true> : output_transform_kernel<N, T, MT, false>;
+    void (*kern)(const MT *, T *, int, int, int, int, int, int, long long, OutShape, int, OutCoef<N>);
+    if (t->symmetric) kern = vec ? output_transform_kernel<N, T, MT, true, true> : output_transform_kernel<N, T, MT, true, false>;
+    else              kern = vec ? output_transform_kernel<N, T, MT, false, true> : output_transform_kernel<N, T, MT, false, false>;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds_bytes, stream,
-                       (const MT *)Mp, (T *)y, g.K, g.H, g.W, g.tiles_h, g.tiles_w, twb, groups,
-                       g.k_blocks, g.T, cols_pitch, k_pitch, (flags & NOVA_FLAG_RELU) ? 1 : 0, coef);
+                       (const MT *)Mp, (T *)y, g.K, g.H, g.W, g.tiles_h, g.tiles_w, g.k_blocks, g.T, sh,
+                       (flags & NOVA_FLAG_RELU) ? 1 : 0, coef);
     return (int)hipGetLastError();
 }
 
