@@ -59,8 +59,8 @@ def main():
     t = nova.nova_make_transforms(points, m, 3)
     U = nova.nova_filter_transform(t, wd)
     ws_bytes = nova.nova_conv2d_workspace_bytes(N, C, H, W, K, m, dt, flags, args.images_per_slab)
-    one_bytes = nova.nova_conv2d_workspace_bytes(N, C, H, W, K, m, dt, flags, 1)
-    slab_imgs = min(N, max(1, ws_bytes // one_bytes))
+    slab_imgs = next(s for s in range(N, 0, -1)
+                     if nova.nova_conv2d_workspace_bytes(N, C, H, W, K, m, dt, flags, s) <= ws_bytes)
     n_slabs = -(-N // slab_imgs)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     y = torch.empty((N, K, H, W), dtype=tdtype, device=dev)
@@ -90,8 +90,9 @@ def main():
     tiles = -(-H // m) * (-(-W // m))
     T_slab = slab_imgs * tiles
     cb, kb = -(-C // 32) * 32, -(-K // 32) * 32
-    V = torch.empty(n * n * T_slab * cb, dtype=tdtype, device=dev)
-    M = torch.empty(n * n * T_slab * kb, dtype=torch.float16 if m_es == 2 else torch.float32, device=dev)
+    V = torch.empty(nova.nova_input_bytes(slab_imgs, C, H, W, m, dt) // es, dtype=tdtype, device=dev)
+    M = torch.empty(nova.nova_product_bytes(slab_imgs, K, H, W, m, dt, flags) // m_es,
+                    dtype=torch.float16 if m_es == 2 else torch.float32, device=dev)
     slabs = [(i, min(slab_imgs, N - i)) for i in range(0, N, slab_imgs)]
     reps = max(10, args.steps)
     marks = []

@@ -101,7 +101,8 @@ int nova_kappa(const nova_transforms *t, double out[4]);
  *   U [n*n][ceil(C/32)][Kp][32]   Kp = K rounded up to a multiple of 32; element (xi, k, c) at
  *                                 ((xi*ceil(C/32) + c/32)*Kp + k)*32 + c%32; padding is zero
  *   V [n*n][ceil(C/32)][T][32]    same with t in place of k and T in place of Kp
- *   M [n*n][ceil(K/32)][T][32]    element (xi, t, k) at ((xi*ceil(K/32) + k/32)*T + t)*32 + k%32
+ *   M [n*n][ceil(K/32)][Tp][32]   Tp = T rounded up to a multiple of 128; element (xi, t, k) at
+ *                                 ((xi*ceil(K/32) + k/32)*Tp + t)*32 + k%32; rows t >= T are scratch
  * U and V have the storage dtype; M is binary32 (binary16 with NOVA_FLAG_M_F16).
  */
 size_t nova_filter_bytes(int K, int C, int m, int dtype);                 /* size of U */
@@ -141,13 +142,15 @@ int nova_winograd_conv2d(const nova_transforms *t, const void *x, const void *U,
                          int N, int C, int H, int W, int K, int dtype, int flags,
                          void *workspace, size_t workspace_bytes, void *stream);
 
-/* The three stages on their own (same arguments; V, M: device buffers of nova_input_bytes /
- * nova_product_bytes for the N images passed).  For tests and per-stage profiling. */
-int nova_input_transform(const nova_transforms *t, const void *x, void *V,
+/* The three stages on their own (same arguments; V, M: device buffers for the N images passed).
+ * V_bytes / M_bytes give the size of the buffer the call writes; the call returns NOVA_ENOSPC
+ * before launching anything if that is less than nova_input_bytes / nova_product_bytes for the
+ * shape (the kernels write whole padded blocks).  For tests and per-stage profiling. */
+int nova_input_transform(const nova_transforms *t, const void *x, void *V, size_t V_bytes,
                          int N, int C, int H, int W, int dtype, void *stream);        /* Sec. 2.1 step 1 */
-int nova_contract(const nova_transforms *t, const void *U, const void *V, void *M,
+int nova_contract(const nova_transforms *t, const void *U, const void *V, void *M, size_t M_bytes,
                   int N, int C, int H, int W, int K, int dtype, int flags, void *stream); /* step 3 + channel sum */
-int nova_output_transform(const nova_transforms *t, const void *M, void *y,
+int nova_output_transform(const nova_transforms *t, const void *M, size_t M_bytes, void *y,
                           int N, int K, int H, int W, int dtype, int flags, void *stream); /* step 4 */
 
 /* out = maxpool2x2(max(in, 0)), stride 2, floor; in [N][C][H][W] -> out [N][C][H/2][W/2] (device).

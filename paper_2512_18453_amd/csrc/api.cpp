@@ -41,7 +41,7 @@ static size_t v_bytes(const Geometry &g, int dtype)
 static size_t m_bytes(const Geometry &g, int dtype, int flags)
 {
     const size_t es = (dtype == NOVA_F16 && (flags & NOVA_FLAG_M_F16)) ? 2 : 4;
-    return (size_t)g.n * g.n * g.k_blocks * (size_t)g.T * kChanBlock * es;
+    return (size_t)g.n * g.n * g.k_blocks * (size_t)g.Tp * kChanBlock * es;
 }
 
 constexpr size_t kDefaultSlabBytes = (size_t)2 << 30;
@@ -74,16 +74,21 @@ extern "C" size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K,
                                               int images_per_slab)
 {
     if (!dims_ok(N, C, H, W, K) || !device_tile_ok(m) || !dtype_ok(dtype) || images_per_slab < 0) return 0;
-    const Geometry one = make_geometry(1, C, H, W, K, m);
-    const size_t per_image = align256(v_bytes(one, dtype)) + align256(m_bytes(one, dtype, flags));
+    auto slab_bytes = [&](long long count) {
+        const Geometry sg = make_geometry((int)count, C, H, W, K, m);
+        return align256(v_bytes(sg, dtype)) + align256(m_bytes(sg, dtype, flags));
+    };
     long long imgs = images_per_slab;
-    if (imgs == 0) {
-        imgs = (long long)(kDefaultSlabBytes / per_image);
-        if (imgs < 1) imgs = 1;
+    if (imgs == 0) {                             // as many images as fit the default budget
+        long long lo = 1, hi = N;
+        while (lo < hi) {
+            const long long mid = (lo + hi + 1) / 2;
+            if (slab_bytes(mid) <= kDefaultSlabBytes) lo = mid; else hi = mid - 1;
+        }
+        imgs = lo;
     }
     if (imgs > N) imgs = N;
-    const Geometry slab = make_geometry((int)imgs, C, H, W, K, m);
-    return align256(v_bytes(slab, dtype)) + align256(m_bytes(slab, dtype, flags));
+    return slab_bytes(imgs);
 }
 
 extern "C" int nova_filter_transform(const nova_transforms *t, const void *w, int K, int C, int dtype,
@@ -94,28 +99,34 @@ extern "C" int nova_filter_transform(const nova_transforms *t, const void *w, in
     return hip_result(launch_filter_transform(t, w, K, C, dtype, U, stream));
 }
 
-extern "C" int nova_input_transform(const nova_transforms *t, const void *x, void *V, int N, int C, int H,
-                                    int W, int dtype, void *stream)
+extern "C" int nova_input_transform(const nova_transforms *t, const void *x, void *V, size_t V_bytes, int N,
+                                    int C, int H, int W, int dtype, void *stream)
 {
     if (int rc = check_handle(t)) return rc;
     if (!x || !V || !dims_ok(N, C, H, W, 1) || !dtype_ok(dtype)) return NOVA_EINVAL;
-    return hip_result(launch_input_transform(t, x, V, make_geometry(N, C, H, W, 1, t->m), dtype, stream));
+    const Geometry g = make_geometry(N, C, H, W, 1, t->m);
+    if (V_bytes < v_bytes(g, dtype)) return NOVA_ENOSPC;
+    return hip_result(launch_input_transform(t, x, V, g, dtype, stream));
 }
 
-extern "C" int nova_contract(const nova_transforms *t, const void *U, const void *V, void *M, int N, int C,
-                             int H, int W, int K, int dtype, int flags, void *stream)
+extern "C" int nova_contract(const nova_transforms *t, const void *U, const void *V, void *M, size_t M_bytes,
+                             int N, int C, int H, int W, int K, int dtype, int flags, void *stream)
 {
     if (int rc = check_handle(t)) return rc;
     if (!U || !V || !M || !dims_ok(N, C, H, W, K) || !dtype_ok(dtype)) return NOVA_EINVAL;
-    return hip_result(launch_contract(t, U, V, M, make_geometry(N, C, H, W, K, t->m), dtype, flags, stream));
+    const Geometry g = make_geometry(N, C, H, W, K, t->m);
+    if (M_bytes < m_bytes(g, dtype, flags)) return NOVA_ENOSPC;
+    return hip_result(launch_contract(t, U, V, M, g, dtype, flags, stream));
 }
 
-extern "C" int nova_output_transform(const nova_transforms *t, const void *M, void *y, int N, int K, int H,
-                                     int W, int dtype, int flags, void *stream)
+extern "C" int nova_output_transform(const nova_transforms *t, const void *M, size_t M_bytes, void *y, int N,
+                                     int K, int H, int W, int dtype, int flags, void *stream)
 {
     if (int rc = check_handle(t)) return rc;
     if (!M || !y || !dims_ok(N, 1, H, W, K) || !dtype_ok(dtype)) return NOVA_EINVAL;
-    return hip_result(launch_output_transform(t, M, y, make_geometry(N, 1, H, W, K, t->m), dtype, flags, stream));
+    const Geometry g = make_geometry(N, 1, H, W, K, t->m);
+    if (M_bytes < m_bytes(g, dtype, flags)) return NOVA_ENOSPC;
+    return hip_result(launch_output_transform(t, M, y, g, dtype, flags, stream));
 }
 
 extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, const void *U, void *y, int N,
@@ -127,18 +138,26 @@ extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, con
     if (((uintptr_t)workspace & 255) != 0) return NOVA_EINVAL;
     const int m = t->m;
 
-    // largest slab (whole images) whose V and M fit the workspace
-    const Geometry one = make_geometry(1, C, H, W, K, m);
-    const size_t v1 = v_bytes(one, dtype), m1 = m_bytes(one, dtype, flags);
-    if (align256(v1) + align256(m1) > workspace_bytes) return NOVA_ENOSPC;
-    long long imgs = (long long)(workspace_bytes / (v1 + m1));
-    if (imgs < 1) imgs = 1;
-    if (imgs > N) imgs = N;
-    while (imgs > 1 && align256(v1 * imgs) + align256(m1 * imgs) > workspace_bytes) --imgs;
+    // largest slab (whole images) whose V and M fit the workspace; slab_bytes grows with the count
+    auto slab_bytes = [&](long long count, size_t *v_part) {
+        const Geometry sg = make_geometry((int)count, C, H, W, K, m);
+        const size_t vb = align256(v_bytes(sg, dtype));
+        if (v_part) *v_part = vb;
+        return vb + align256(m_bytes(sg, dtype, flags));
+    };
+    if (slab_bytes(1, nullptr) > workspace_bytes) return NOVA_ENOSPC;
+    long long lo = 1, hi = N;                    // invariant: lo fits
+    while (lo < hi) {
+        const long long mid = (lo + hi + 1) / 2;
+        if (slab_bytes(mid, nullptr) <= workspace_bytes) lo = mid; else hi = mid - 1;
+    }
+    const long long imgs = lo;
+    size_t v_part = 0;
+    (void)slab_bytes(imgs, &v_part);
 
     const size_t es = dtype_size(dtype);
     char *Vbuf = (char *)workspace;
-    char *Mbuf = Vbuf + align256(v1 * (size_t)imgs);
+    char *Mbuf = Vbuf + v_part;
     for (int n0 = 0; n0 < N; n0 += (int)imgs) {
         const int nb = (N - n0 < imgs) ? N - n0 : (int)imgs;
         const Geometry g = make_geometry(nb, C, H, W, K, m);

@@ -23,7 +23,7 @@ constexpr int kRowHalves = 40;   // LDS row pitch of a 32-channel operand row, i
 template <int BM, int BN, int WM, int WN, typename MT>
 __global__ void __launch_bounds__(256)
 contract_f16_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__restrict__ Mo,
-                    int T, int Kp, int c_blocks, int k_blocks, int row_blocks, int col_blocks)
+                    int T, int Tp, int Kp, int c_blocks, int k_blocks, int row_blocks, int col_blocks)
 {
     constexpr int MB = BM / WM / 32;          // 32x32 MFMA blocks per wave, rows
     constexpr int NB = BN / WN / 32;          // and columns
@@ -125,7 +125,7 @@ contract_f16_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__
     for (int j = 0; j < NB; ++j) {
         const int kb = (k0 >> 5) + wn * NB + j;
         if (kb >= k_blocks) continue;
-        MT *dst = Mo + ((size_t)xi * k_blocks + kb) * (size_t)T * kChanBlock + col;
+        MT *dst = Mo + ((size_t)xi * k_blocks + kb) * (size_t)Tp * kChanBlock + col;
 #pragma unroll
         for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -136,10 +136,161 @@ contract_f16_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Weight-stationary variant (the one used whenever the shape allows).
+//
+// The contraction is bound by HBM traffic (V in, M out), not by the matrix cores, and a tiled
+// GEMM that reloads U and V per output tile is held back by load latency: it never has enough
+// bytes in flight.  Here a persistent workgroup (one per CU) keeps its slice of U[xi] -- 64
+// output channels x all C input channels per wave -- in VGPRs as ready-made MFMA B-fragments,
+// and streams V through LDS exactly once: a stage is SR = 32*WM consecutive tiles t with all C
+// channels, so each stage yields finished outputs (no accumulation across stages) which go
+// straight from the accumulators to M.  The loads of the next D stages are kept in flight in
+// registers while the current stage is multiplied; work items (k-group, xi, stage) are dealt to
+// the workgroups in contiguous, equal ranges, so U fragments are reloaded only when xi changes.
+//   WN waves split the output channels (WN*64 per workgroup), WM = 4/WN waves split the rows.
+//   CB = C/32 (fixes the registers for the U fragments), D = stages in flight.
+template <int WN, int CB, int D, typename MT>
+__global__ void __launch_bounds__(256, 1)
+contract_stationary_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__restrict__ Mo,
+                           int T, int Tp, int Kp, int k_blocks, int stages_per_xi, int xi_count, int items_total)
+{
+    constexpr int WM = 4 / WN;
+    constexpr int SR = 32 * WM;                  // rows (tiles t) per stage
+    constexpr int NP = CB * SR * 4 / 256;        // 16-byte pieces per thread and stage
+    constexpr int STAGE_HALVES = CB * SR * kRowHalves;
+    static_assert(NP >= 1 && (D == 1 || D == 2 || D == 4), "pipeline shape");
+    typedef float float4v __attribute__((ext_vector_type(4)));
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+
+    __shared__ __align__(16) f16 lds_a[2][STAGE_HALVES];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave / WN, wn = wave % WN;
+    const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+
+    // contiguous, equal share of the work items; item = ((kg * xi_count) + xi) * stages_per_xi + tb
+    const int g0 = (int)((long long)items_total * blockIdx.x / gridDim.x);
+    const int g1 = (int)((long long)items_total * (blockIdx.x + 1) / gridDim.x);
+    if (g0 >= g1) return;
+    const int per_kg = xi_count * stages_per_xi;
+
+    // per-thread pieces of a stage: piece p -> (channel block, row, 16-byte piece of the 64-byte row)
+    int p_row[NP];
+    size_t p_off[NP];
+    int p_lds[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+        const int p = tid + i * 256;
+        const int cb = p / (SR * 4);
+        p_row[i] = (p >> 2) % SR;
+        p_off[i] = (size_t)cb * T * kChanBlock + (p & 3) * 8;
+        p_lds[i] = (cb * SR + p_row[i]) * kRowHalves + (p & 3) * 8;
+    }
+
+    // Everything on the common path below issues a fixed number of memory instructions: the
+    // hardware counts loads and stores in one in-order counter, and a conditional load or store
+    // would force the wait before an LDS write to drain the younger prefetches as well.
+    uint4v regs[D][NP];
+    auto issue_stage = [&](int g, uint4v (&dst)[NP]) {
+        if (g > g1 - 1) g = g1 - 1;                                    // tail: refetch the last stage
+        const int rem = g % per_kg;
+        const int xi = rem / stages_per_xi, tb = rem - xi * stages_per_xi;
+        const f16 *base = V + (size_t)xi * CB * T * kChanBlock;
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+            int t = tb * SR + p_row[i]; if (t > T - 1) t = T - 1;      // rows past the end: reread the last
+            dst[i] = *reinterpret_cast<const uint4v *>(base + p_off[i] + (size_t)t * kChanBlock);
+        }
+    };
+    auto land_stage = [&](int buf, const uint4v (&src)[NP]) {
+#pragma unroll
+        for (int i = 0; i < NP; ++i) *reinterpret_cast<uint4v *>(&lds_a[buf][p_lds[i]]) = src[i];
+    };
+
+    half8 ufrag[2][CB][2];                        // this wave's 64 output channels x all C channels of U[xi]
+    int held = -1;                                // item / stages_per_xi of the fragments held
+    auto load_u = [&](int kg, int xi) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            const int k = (kg * WN + wn) * 64 + nb * 32 + frag_row;       // < Kp: Kp is a multiple of WN*64
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk)
+                    ufrag[nb][cb][kk] = *reinterpret_cast<const half8 *>(
+                        U + (((size_t)xi * CB + cb) * Kp + k) * kChanBlock + kk * 16 + frag_k);
+        }
+    };
+
+    // prologue: D stages in flight, the first one landed
+#pragma unroll
+    for (int d = 0; d < D; ++d) issue_stage(g0 + d, regs[d]);
+    land_stage(0, regs[0]);
+    __syncthreads();
+
+    for (int base = g0; base < g1; base += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int g = base + d;
+            if (g >= g1) break;
+            const int buf = (g - g0) & 1;
+            issue_stage(g + D, regs[d]);                       // slot d was landed one item ago
+
+            const int seg = g / stages_per_xi;                 // = kg * xi_count + xi
+            const int kg = seg / xi_count, xi = seg - kg * xi_count, tb = g - seg * stages_per_xi;
+            if (seg != held) {
+                load_u(kg, xi);
+                held = seg;
+                // wait here, inside the branch: otherwise the waits for these loads are placed after
+                // the join, where they would also drain the prefetched stages on the common path
+                __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
+            }
+
+            // acc[nb] = U-block (32 output channels) x V-stage rows (32 tiles): D[row = k][col = t]
+            float16v acc[2];
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[nb][e] = 0.0f;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk) {
+                    const half8 vf = *reinterpret_cast<const half8 *>(
+                        &lds_a[buf][(cb * SR + wm * 32 + frag_row) * kRowHalves + kk * 16 + frag_k]);
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ufrag[0][cb][kk], vf, acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ufrag[1][cb][kk], vf, acc[1], 0, 0, 0);
+                }
+            land_stage(buf ^ 1, regs[(d + 1) % D]);
+
+            // lane holds t = lane%32 and output channels 8*(e/4) + 4*(lane/32) + e%4 of each block:
+            // four consecutive channels per store; rows up to Tp exist, so no store is conditional
+            const int t = tb * SR + wm * 32 + frag_row;
+            MT *dst = Mo + (((size_t)xi * k_blocks + (kg * WN + wn) * 2) * Tp + t) * kChanBlock + (lane >> 5) * 4;
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    MT *out = dst + (size_t)nb * Tp * kChanBlock + q * 8;
+                    if constexpr (sizeof(MT) == 4) {
+                        *reinterpret_cast<float4v *>(out) =
+                            float4v{acc[nb][4 * q], acc[nb][4 * q + 1], acc[nb][4 * q + 2], acc[nb][4 * q + 3]};
+                    } else {
+                        *reinterpret_cast<half4 *>(out) =
+                            half4{(f16)acc[nb][4 * q], (f16)acc[nb][4 * q + 1], (f16)acc[nb][4 * q + 2],
+                                  (f16)acc[nb][4 * q + 3]};
+                    }
+                }
+            __syncthreads();
+        }
+    }
+}
+
 // binary32: 64 x 64 tile, 256 threads, 4 x 4 outputs per thread
 __global__ void __launch_bounds__(256)
 contract_f32_kernel(const float *__restrict__ U, const float *__restrict__ V, float *__restrict__ Mo,
-                    int T, int Kp, int c_blocks, int k_blocks, int row_blocks, int col_blocks)
+                    int T, int Tp, int Kp, int c_blocks, int k_blocks, int row_blocks, int col_blocks)
 {
     __shared__ float lds_a[64][kChanBlock + 1];
     __shared__ float lds_b[64][kChanBlock + 1];
@@ -178,7 +329,7 @@ contract_f32_kernel(const float *__restrict__ U, const float *__restrict__ V, fl
         for (int j = 0; j < 4; ++j) {
             const int t = t0 + ty + 16 * i, k = k0 + tx + 16 * j;
             if (t < T && (k >> 5) < k_blocks)
-                Mo[(((size_t)xi * k_blocks + (k >> 5)) * T + t) * kChanBlock + (k & 31)] = acc[i][j];
+                Mo[(((size_t)xi * k_blocks + (k >> 5)) * Tp + t) * kChanBlock + (k & 31)] = acc[i][j];
         }
 }
 
@@ -189,17 +340,57 @@ static int launch_c16(const void *U, const void *V, void *Mo, const Geometry &g,
     const long long blocks = (long long)g.n * g.n * row_blocks * col_blocks;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
     hipLaunchKernelGGL((contract_f16_kernel<BM, BN, WM, WN, MT>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                       (const f16 *)U, (const f16 *)V, (MT *)Mo, (int)g.T, g.Kp, g.c_blocks, g.k_blocks,
+                       (const f16 *)U, (const f16 *)V, (MT *)Mo, (int)g.T, (int)g.Tp, g.Kp, g.c_blocks, g.k_blocks,
                        row_blocks, col_blocks);
     return (int)hipGetLastError();
+}
+
+template <int WN, int CB, int D, typename MT>
+static int launch_stationary(const void *U, const void *V, void *Mo, const Geometry &g, hipStream_t stream)
+{
+    constexpr int SR = 32 * (4 / WN);
+    static int cu_count = 0;
+    if (cu_count == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cu_count = n;
+    }
+    const int stages_per_xi = ceil_div((int)g.T, SR);
+    const int kgroups = g.Kp / (WN * 64);
+    const long long items = (long long)kgroups * g.n * g.n * stages_per_xi;
+    if (items <= 0 || items > 0x7fffffffLL) return (int)hipErrorInvalidValue;
+    const int blocks = (int)(items < cu_count ? items : cu_count);
+    hipLaunchKernelGGL((contract_stationary_kernel<WN, CB, D, MT>), dim3(blocks), dim3(256), 0, stream,
+                       (const f16 *)U, (const f16 *)V, (MT *)Mo, (int)g.T, (int)g.Tp, g.Kp, g.k_blocks,
+                       stages_per_xi, g.n * g.n, (int)items);
+    return (int)hipGetLastError();
+}
+
+template <typename MT>
+static int launch_c16_tiled(const void *U, const void *V, void *Mo, const Geometry &g, hipStream_t s)
+{
+    if (g.Kp >= 128) return launch_c16<128, 128, 2, 2, MT>(U, V, Mo, g, s);
+    if (g.Kp >= 64) return launch_c16<128, 64, 2, 2, MT>(U, V, Mo, g, s);
+    return launch_c16<128, 32, 4, 1, MT>(U, V, Mo, g, s);
 }
 
 template <typename MT>
 static int launch_c16_shape(const void *U, const void *V, void *Mo, const Geometry &g, hipStream_t s)
 {
-    if (g.Kp >= 128) return launch_c16<128, 128, 2, 2, MT>(U, V, Mo, g, s);
-    if (g.Kp >= 64) return launch_c16<128, 64, 2, 2, MT>(U, V, Mo, g, s);
-    return launch_c16<128, 32, 4, 1, MT>(U, V, Mo, g, s);
+    // weight-stationary kernel: C in {64, 128, 256} and K a multiple of the workgroup's channel span
+    const int cb = g.c_blocks;
+    const int wn = g.Kp % 256 == 0 ? 4 : g.Kp % 128 == 0 ? 2 : g.Kp % 64 == 0 ? 1 : 0;
+    if (wn == 4 && cb == 8) return launch_stationary<4, 8, 4, MT>(U, V, Mo, g, s);
+    if (wn == 4 && cb == 4) return launch_stationary<4, 4, 4, MT>(U, V, Mo, g, s);
+    if (wn == 4 && cb == 2) return launch_stationary<4, 2, 4, MT>(U, V, Mo, g, s);
+    if (wn == 2 && cb == 8) return launch_stationary<2, 8, 2, MT>(U, V, Mo, g, s);
+    if (wn == 2 && cb == 4) return launch_stationary<2, 4, 4, MT>(U, V, Mo, g, s);
+    if (wn == 2 && cb == 2) return launch_stationary<2, 2, 4, MT>(U, V, Mo, g, s);
+    if (wn == 1 && cb == 4) return launch_stationary<1, 4, 2, MT>(U, V, Mo, g, s);
+    if (wn == 1 && cb == 2) return launch_stationary<1, 2, 4, MT>(U, V, Mo, g, s);
+    return launch_c16_tiled<MT>(U, V, Mo, g, s);       // other shapes: tiled kernel
 }
 
 int launch_contract(const nova_transforms *, const void *U, const void *V, void *Mo, const Geometry &g,
@@ -214,7 +405,7 @@ int launch_contract(const nova_transforms *, const void *U, const void *V, void 
     const long long blocks = (long long)g.n * g.n * row_blocks * col_blocks;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
     hipLaunchKernelGGL(contract_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const float *)U,
-                       (const float *)V, (float *)Mo, (int)g.T, g.Kp, g.c_blocks, g.k_blocks, row_blocks,
+                       (const float *)V, (float *)Mo, (int)g.T, (int)g.Tp, g.Kp, g.c_blocks, g.k_blocks, row_blocks,
                        col_blocks);
     return (int)hipGetLastError();
 }

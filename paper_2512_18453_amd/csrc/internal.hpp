@@ -51,6 +51,7 @@ struct Geometry {
     int N, C, H, W, K, m, n;
     int tiles_h, tiles_w;
     long long T;          // tiles in the batch
+    long long Tp;         // T rounded up to a multiple of 128: row count of M (rows >= T are scratch)
     int c_blocks, k_blocks;
     int Kp;               // K rounded up to the channel block
 };
@@ -64,6 +65,7 @@ inline Geometry make_geometry(int N, int C, int H, int W, int K, int m)
     g.tiles_h = ceil_div(H, m);
     g.tiles_w = ceil_div(W, m);
     g.T = (long long)N * g.tiles_h * g.tiles_w;
+    g.Tp = (g.T + 127) / 128 * 128;
     g.c_blocks = ceil_div(C, kChanBlock);
     g.k_blocks = ceil_div(K, kChanBlock);
     g.Kp = g.k_blocks * kChanBlock;

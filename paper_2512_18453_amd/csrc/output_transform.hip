@@ -1,5 +1,6 @@
 // Output transform Y = A^T M A (Sec. 2.1 step 4, nested in 2D), cropped to H x W and written as
-// y [N][K][H][W];  M [n*n][K/32][T][32] holds the channel-summed products.
+// y [N][K][H][W];  M [n*n][K/32][Tp][32] holds the channel-summed products (Tp = T rounded up to
+// a multiple of 128; the extra rows are never read).
 //
 // One workgroup takes one image, one tile row, a group of TWB neighbouring tiles and one block of
 // 32 output channels; thread = one tile x one channel, so the n*n loads of a half-wave are 128
@@ -185,7 +186,7 @@ static int launch_ot(const nova_transforms *t, const void *Mp, void *y, const Ge
     if (t->symmetric) kern = vec ? output_transform_kernel<N, T, MT, true, true> : output_transform_kernel<N, T, MT, true, false>;
     else              kern = vec ? output_transform_kernel<N, T, MT, false, true> : output_transform_kernel<N, T, MT, false, false>;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds_bytes, stream,
-                       (const MT *)Mp, (T *)y, g.K, g.H, g.W, g.tiles_h, g.tiles_w, g.k_blocks, g.T, sh,
+                       (const MT *)Mp, (T *)y, g.K, g.H, g.W, g.tiles_h, g.tiles_w, g.k_blocks, g.Tp, sh,
                        (flags & NOVA_FLAG_RELU) ? 1 : 0, coef);
     return (int)hipGetLastError();
 }

@@ -67,9 +67,9 @@ def lib():
         L.nova_conv2d_workspace_bytes.restype = sz
         L.nova_filter_transform.argtypes = [vp, vp, i, i, i, vp, vp]
         L.nova_winograd_conv2d.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp]
-        L.nova_input_transform.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
-        L.nova_contract.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
-        L.nova_output_transform.argtypes = [vp, vp, vp, i, i, i, i, i, i, vp]
+        L.nova_input_transform.argtypes = [vp, vp, vp, sz, i, i, i, i, i, vp]
+        L.nova_contract.argtypes = [vp, vp, vp, vp, sz, i, i, i, i, i, i, i, vp]
+        L.nova_output_transform.argtypes = [vp, vp, sz, vp, i, i, i, i, i, i, vp]
         L.nova_relu_maxpool2x2.argtypes = [vp, vp, i, i, i, i, i, vp]
         L.nova_strerror.argtypes = [i]
         L.nova_strerror.restype = ctypes.c_char_p
@@ -206,7 +206,8 @@ def nova_input_transform(t, x, V=None):
     dt = _dtype_code(x)
     if V is None:
         V = torch.empty(nova_input_bytes(N, C, H, W, t.m, dt) // x.element_size(), dtype=x.dtype, device=x.device)
-    _check(lib().nova_input_transform(t.handle, _dev(x), _dev(V), N, C, H, W, dt, _stream()), "nova_input_transform")
+    _check(lib().nova_input_transform(t.handle, _dev(x), _dev(V), V.numel() * V.element_size(), N, C, H, W, dt,
+                                      _stream()), "nova_input_transform")
     return V
 
 
@@ -216,7 +217,8 @@ def nova_contract(t, U, V, N, C, H, W, K, flags=0, M=None):
         m_dtype = torch.float16 if (dt == NOVA_F16 and flags & NOVA_FLAG_M_F16) else torch.float32
         nbytes = nova_product_bytes(N, K, H, W, t.m, dt, flags)
         M = torch.empty(nbytes // (2 if m_dtype == torch.float16 else 4), dtype=m_dtype, device=V.device)
-    _check(lib().nova_contract(t.handle, _dev(U), _dev(V), _dev(M), N, C, H, W, K, dt, flags, _stream()), "nova_contract")
+    _check(lib().nova_contract(t.handle, _dev(U), _dev(V), _dev(M), M.numel() * M.element_size(), N, C, H, W, K, dt,
+                               flags, _stream()), "nova_contract")
     return M
 
 
@@ -225,7 +227,8 @@ def nova_output_transform(t, M, N, K, H, W, dtype, flags=0, y=None):
     dt = NOVA_F16 if dtype == torch.float16 else NOVA_F32
     if y is None:
         y = torch.empty((N, K, H, W), dtype=dtype, device=M.device)
-    _check(lib().nova_output_transform(t.handle, _dev(M), _dev(y), N, K, H, W, dt, flags, _stream()), "nova_output_transform")
+    _check(lib().nova_output_transform(t.handle, _dev(M), M.numel() * M.element_size(), _dev(y), N, K, H, W, dt,
+                                       flags, _stream()), "nova_output_transform")
     return y
 
 

@@ -73,7 +73,8 @@ def run_stages(t, x, w, flags=0):
     Kp = -(-K // 32) * 32
     Ul = unblock(U, n2, Kp, C)
     assert not Ul[:, K:, :].any()                       # padding rows are zero
-    out = dict(U=Ul[:, :K, :], V=unblock(V, n2, T, C), M=unblock(M, n2, T, K),
+    Tp = -(-T // 128) * 128                             # M has Tp rows per block; rows >= T are scratch
+    out = dict(U=Ul[:, :K, :], V=unblock(V, n2, T, C), M=unblock(M, n2, Tp, K)[:, :T, :],
                y=y.cpu().numpy().astype(np.float64), y_conv=y2.cpu().numpy().astype(np.float64))
     return out
 
