@@ -10,6 +10,8 @@
 // LDS (rows padded from 64 to 80 bytes, which spreads the 16 lanes of a 128-bit read phase over
 // all 64 banks), global loads for step s+1 are issued before the MFMAs of step s.
 // binary32 path: same layouts, plain FMA tiles (validation path, not tuned).
+#include <type_traits>
+
 #include "device_common.hpp"
 
 namespace nova {
@@ -150,6 +152,40 @@ contract_f16_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__
 // the workgroups in contiguous, equal ranges, so U fragments are reloaded only when xi changes.
 //   WN waves split the output channels (WN*64 per workgroup), WM = 4/WN waves split the rows.
 //   CB = C/32 (fixes the registers for the U fragments), D = stages in flight.
+// The compiler's own wait-count bookkeeping merges the pipeline state at the loop header with the
+// (store-free) prologue and then waits for all but the newest stage, which defeats the prefetch.
+// The streaming loads and the stores of this kernel are therefore issued through inline assembly,
+// invisible to that bookkeeping, and waited for with explicit counts.  The hardware retires vector
+// memory operations of a wave in issue order, so "at most X outstanding" guarantees completion of
+// every operation that has at least X younger ones.
+__device__ __forceinline__ uint4v stream_load16(const void *p)
+{
+    uint4v v;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+__device__ __forceinline__ void stream_store(float *p, float a, float b, float c, float d)
+{
+    typedef float float4v __attribute__((ext_vector_type(4)));
+    const float4v v = {a, b, c, d};
+    asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void stream_store(f16 *p, float a, float b, float c, float d)
+{
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    const half4 v = {(f16)a, (f16)b, (f16)c, (f16)d};
+    asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(p), "v"(v) : "memory");
+}
+// wait until at most X vector memory operations are outstanding, and make the registers of `r`
+// depend on the wait so that no use of them is scheduled above it
+template <int X, int NP>
+__device__ __forceinline__ void stream_wait(uint4v (&r)[NP])
+{
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(X) : "memory");
+#pragma unroll
+    for (int i = 0; i < NP; ++i) asm volatile("" : "+v"(r[i]));
+}
+
 template <int WN, int CB, int D, typename MT>
 __global__ void __launch_bounds__(256, 1)
 contract_stationary_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__restrict__ Mo,
@@ -157,11 +193,11 @@ contract_stationary_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V,
 {
     constexpr int WM = 4 / WN;
     constexpr int SR = 32 * WM;                  // rows (tiles t) per stage
-    constexpr int NP = CB * SR * 4 / 256;        // 16-byte pieces per thread and stage
+    constexpr int NP = CB * SR * 4 / 256;        // 16-byte loads per thread and stage
+    constexpr int NS = 8;                        // stores per thread and stage
     constexpr int STAGE_HALVES = CB * SR * kRowHalves;
     static_assert(NP >= 1 && (D == 1 || D == 2 || D == 4), "pipeline shape");
-    typedef float float4v __attribute__((ext_vector_type(4)));
-    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    static_assert((D - 1) * (NP + NS) <= 63, "wait count must fit the 6-bit counter");
 
     __shared__ __align__(16) f16 lds_a[2][STAGE_HALVES];
 
@@ -188,11 +224,10 @@ contract_stationary_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V,
         p_lds[i] = (cb * SR + p_row[i]) * kRowHalves + (p & 3) * 8;
     }
 
-    // Everything on the common path below issues a fixed number of memory instructions: the
-    // hardware counts loads and stores in one in-order counter, and a conditional load or store
-    // would force the wait before an LDS write to drain the younger prefetches as well.
+    // Every stage issues exactly NP loads and NS stores per thread (nothing conditional), which is
+    // what the explicit wait counts below rely on.
     uint4v regs[D][NP];
-    auto issue_stage = [&](int g, uint4v (&dst)[NP]) {
+    auto issue_stage = [&](int g, uint4v (&dst)[NP]) __attribute__((always_inline)) {
         if (g > g1 - 1) g = g1 - 1;                                    // tail: refetch the last stage
         const int rem = g % per_kg;
         const int xi = rem / stages_per_xi, tb = rem - xi * stages_per_xi;
@@ -200,17 +235,17 @@ contract_stationary_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V,
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
             int t = tb * SR + p_row[i]; if (t > T - 1) t = T - 1;      // rows past the end: reread the last
-            dst[i] = *reinterpret_cast<const uint4v *>(base + p_off[i] + (size_t)t * kChanBlock);
+            dst[i] = stream_load16(base + p_off[i] + (size_t)t * kChanBlock);
         }
     };
-    auto land_stage = [&](int buf, const uint4v (&src)[NP]) {
+    auto land_stage = [&](int buf, const uint4v (&src)[NP]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < NP; ++i) *reinterpret_cast<uint4v *>(&lds_a[buf][p_lds[i]]) = src[i];
     };
 
     half8 ufrag[2][CB][2];                        // this wave's 64 output channels x all C channels of U[xi]
     int held = -1;                                // item / stages_per_xi of the fragments held
-    auto load_u = [&](int kg, int xi) {
+    auto load_u = [&](int kg, int xi) __attribute__((always_inline)) {
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
             const int k = (kg * WN + wn) * 64 + nb * 32 + frag_row;       // < Kp: Kp is a multiple of WN*64
@@ -223,68 +258,89 @@ contract_stationary_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V,
         }
     };
 
-    // prologue: D stages in flight, the first one landed
+    // One work item.  YOUNGER = operations issued after the loads of stage g+1 at the point of
+    // the wait: (D-1) stages of loads, and the stores of the stages completed since.
+    auto do_stage = [&](int g, uint4v (&slot_next)[NP], uint4v (&slot_land)[NP], auto younger) __attribute__((always_inline)) {
+        constexpr int YOUNGER = decltype(younger)::value;
+        const int buf = (g - g0) & 1;
+        issue_stage(g + D, slot_next);                     // this slot was landed one item ago
+
+        const int seg = g / stages_per_xi;                 // = kg * xi_count + xi
+        const int kg = seg / xi_count, xi = seg - kg * xi_count, tb = g - seg * stages_per_xi;
+        if (seg != held) {
+            load_u(kg, xi);
+            held = seg;
+            // wait inside the branch, or the compiler's waits for these loads land after the join
+            __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
+        }
+
+        // acc[nb] = U-block (32 output channels) x V-stage rows (32 tiles): D[row = k][col = t]
+        float16v acc[2];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[nb][e] = 0.0f;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const half8 vf = *reinterpret_cast<const half8 *>(
+                    &lds_a[buf][(cb * SR + wm * 32 + frag_row) * kRowHalves + kk * 16 + frag_k]);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ufrag[0][cb][kk], vf, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ufrag[1][cb][kk], vf, acc[1], 0, 0, 0);
+            }
+        stream_wait<YOUNGER, NP>(slot_land);
+        land_stage(buf ^ 1, slot_land);
+
+        // lane holds t = lane%32 and output channels 8*(e/4) + 4*(lane/32) + e%4 of each block:
+        // four consecutive channels per store; rows up to Tp exist, so no store is conditional
+        const int t = tb * SR + wm * 32 + frag_row;
+        MT *dst = Mo + (((size_t)xi * k_blocks + (kg * WN + wn) * 2) * Tp + t) * kChanBlock + (lane >> 5) * 4;
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                stream_store(dst + (size_t)nb * Tp * kChanBlock + q * 8, acc[nb][4 * q], acc[nb][4 * q + 1],
+                             acc[nb][4 * q + 2], acc[nb][4 * q + 3]);
+        __syncthreads();
+    };
+
+    // prologue: D stages in flight, the first one landed (its D-1 successors are younger)
 #pragma unroll
     for (int d = 0; d < D; ++d) issue_stage(g0 + d, regs[d]);
+    stream_wait<(D - 1) * NP, NP>(regs[0]);
     land_stage(0, regs[0]);
     __syncthreads();
 
-    for (int base = g0; base < g1; base += D) {
-#pragma unroll
-        for (int d = 0; d < D; ++d) {
-            const int g = base + d;
-            if (g >= g1) break;
-            const int buf = (g - g0) & 1;
-            issue_stage(g + D, regs[d]);                       // slot d was landed one item ago
-
-            const int seg = g / stages_per_xi;                 // = kg * xi_count + xi
-            const int kg = seg / xi_count, xi = seg - kg * xi_count, tb = g - seg * stages_per_xi;
-            if (seg != held) {
-                load_u(kg, xi);
-                held = seg;
-                // wait here, inside the branch: otherwise the waits for these loads are placed after
-                // the join, where they would also drain the prefetched stages on the common path
-                __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
-            }
-
-            // acc[nb] = U-block (32 output channels) x V-stage rows (32 tiles): D[row = k][col = t]
-            float16v acc[2];
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[nb][e] = 0.0f;
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk) {
-                    const half8 vf = *reinterpret_cast<const half8 *>(
-                        &lds_a[buf][(cb * SR + wm * 32 + frag_row) * kRowHalves + kk * 16 + frag_k]);
-                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ufrag[0][cb][kk], vf, acc[0], 0, 0, 0);
-                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ufrag[1][cb][kk], vf, acc[1], 0, 0, 0);
-                }
-            land_stage(buf ^ 1, regs[(d + 1) % D]);
-
-            // lane holds t = lane%32 and output channels 8*(e/4) + 4*(lane/32) + e%4 of each block:
-            // four consecutive channels per store; rows up to Tp exist, so no store is conditional
-            const int t = tb * SR + wm * 32 + frag_row;
-            MT *dst = Mo + (((size_t)xi * k_blocks + (kg * WN + wn) * 2) * Tp + t) * kChanBlock + (lane >> 5) * 4;
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    MT *out = dst + (size_t)nb * Tp * kChanBlock + q * 8;
-                    if constexpr (sizeof(MT) == 4) {
-                        *reinterpret_cast<float4v *>(out) =
-                            float4v{acc[nb][4 * q], acc[nb][4 * q + 1], acc[nb][4 * q + 2], acc[nb][4 * q + 3]};
-                    } else {
-                        *reinterpret_cast<half4 *>(out) =
-                            half4{(f16)acc[nb][4 * q], (f16)acc[nb][4 * q + 1], (f16)acc[nb][4 * q + 2],
-                                  (f16)acc[nb][4 * q + 3]};
-                    }
-                }
-            __syncthreads();
+    // first D items: the stores issued so far number d * NS, not yet (D-1) * NS.  The slot indices
+    // must be compile-time constants (register arrays), hence the spelled-out sequence.
+    auto first_item = [&](auto dtag) __attribute__((always_inline)) {
+        constexpr int d = decltype(dtag)::value;
+        do_stage(g0 + d, regs[d], regs[(d + 1) % D],
+                 std::integral_constant<int, (D - 1) * NP + (d < D - 1 ? d : D - 1) * NS>{});
+    };
+    auto steady_item = [&](int g, auto dtag) __attribute__((always_inline)) {
+        constexpr int d = decltype(dtag)::value;
+        do_stage(g, regs[d], regs[(d + 1) % D], std::integral_constant<int, (D - 1) * (NP + NS)>{});
+    };
+    using std::integral_constant;
+    do {
+        first_item(integral_constant<int, 0>{});
+        if constexpr (D > 1) { if (g0 + 1 >= g1) break; first_item(integral_constant<int, 1>{}); }
+        if constexpr (D > 2) {
+            if (g0 + 2 >= g1) break; first_item(integral_constant<int, 2>{});
+            if (g0 + 3 >= g1) break; first_item(integral_constant<int, 3>{});
+        }
+    } while (false);
+    for (int base = g0 + D; base < g1; base += D) {
+        steady_item(base, integral_constant<int, 0>{});
+        if constexpr (D > 1) { if (base + 1 >= g1) break; steady_item(base + 1, integral_constant<int, 1>{}); }
+        if constexpr (D > 2) {
+            if (base + 2 >= g1) break; steady_item(base + 2, integral_constant<int, 2>{});
+            if (base + 3 >= g1) break; steady_item(base + 3, integral_constant<int, 3>{});
         }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // surplus tail prefetches and the last stores
 }
 
 // binary32: 64 x 64 tile, 256 threads, 4 x 4 outputs per thread

@@ -88,6 +88,16 @@ SMALL_FP16 = [
     ("nova", 6, 2, 40, 130, 56, 56),
     ("nova", 8, 3, 72, 96, 56, 56),
     ("nova", 8, 1, 3, 5, 17, 70),
+    # shapes that take the weight-stationary contraction (C in {64,128,256}, K a multiple of 64),
+    # one per (waves along K, channel blocks) variant, with ragged last stages
+    ("nova", 4, 2, 64, 64, 20, 20),
+    ("nova", 6, 3, 128, 128, 30, 27),
+    ("nova", 8, 2, 256, 256, 33, 40),
+    ("nova", 8, 5, 64, 256, 56, 56),
+    ("nova", 6, 2, 256, 128, 24, 24),
+    ("nova", 4, 1, 128, 64, 64, 64),
+    ("standard", 4, 1, 256, 512, 16, 16),
+    ("nova", 8, 1, 128, 256, 17, 17),
 ]
 
 
