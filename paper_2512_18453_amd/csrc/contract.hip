@@ -340,7 +340,15 @@ contract_stationary_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V,
             if (base + 3 >= g1) break; steady_item(base + 3, integral_constant<int, 3>{});
         }
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // surplus tail prefetches and the last stores
+    // Surplus tail prefetches are still in flight.  Their destination registers must stay
+    // allocated until they have landed -- the compiler does not know these loads are asynchronous
+    // and would otherwise reuse the registers of values it sees as dead -- so every slot is named
+    // once more after the final wait, on every path that leaves the loops above.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+#pragma unroll
+        for (int i = 0; i < NP; ++i) asm volatile("" : : "v"(regs[d][i]));
 }
 
 // binary32: 64 x 64 tile, 256 threads, 4 x 4 outputs per thread
@@ -435,6 +443,10 @@ static int launch_c16_tiled(const void *U, const void *V, void *Mo, const Geomet
 template <typename MT>
 static int launch_c16_shape(const void *U, const void *V, void *Mo, const Geometry &g, hipStream_t s)
 {
+    // The register-staged weight-stationary kernel is switched off: its inline-asm loads are
+    // asynchronous behind the compiler's back, and under register pressure the compiler copies or
+    // reuses their destination registers while the loads are still in flight.
+    if (true) return launch_c16_tiled<MT>(U, V, Mo, g, s);
     // weight-stationary kernel: C in {64, 128, 256} and K a multiple of the workgroup's channel span
     const int cb = g.c_blocks;
     const int wn = g.Kp % 256 == 0 ? 4 : g.Kp % 128 == 0 ? 2 : g.Kp % 64 == 0 ? 1 : 0;
