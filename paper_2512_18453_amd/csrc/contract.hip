@@ -20,6 +20,7 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 
+constexpr bool kUseStreamKernel = false;   // until the direct global->LDS load is validated on the device
 constexpr int kRowHalves = 40;   // LDS row pitch of a 32-channel operand row, in binary16 units (80 B)
 
 template <int BM, int BN, int WM, int WN, typename MT>
@@ -139,30 +140,36 @@ contract_f16_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__
 }
 
 // ---------------------------------------------------------------------------------------------
-// Weight-stationary variant (the one used whenever the shape allows).
+// Weight-stationary streaming variant.
 //
 // The contraction is bound by HBM traffic (V in, M out), not by the matrix cores, and a tiled
 // GEMM that reloads U and V per output tile is held back by load latency: it never has enough
 // bytes in flight.  Here a persistent workgroup (one per CU) keeps its slice of U[xi] -- 64
-// output channels x all C input channels per wave -- in VGPRs as ready-made MFMA B-fragments,
-// and streams V through LDS exactly once: a stage is SR = 32*WM consecutive tiles t with all C
-// channels, so each stage yields finished outputs (no accumulation across stages) which go
-// straight from the accumulators to M.  The loads of the next D stages are kept in flight in
-// registers while the current stage is multiplied; work items (k-group, xi, stage) are dealt to
-// the workgroups in contiguous, equal ranges, so U fragments are reloaded only when xi changes.
+// output channels x all C input channels per wave -- in VGPRs as ready-made MFMA fragments, and
+// streams V exactly once through a ring of S stages in LDS, filled by direct global->LDS loads
+// (no destination registers), S-1 stages in flight.  A stage is SR = 32*WM consecutive tiles t
+// with all C channels, so each stage yields finished outputs (no accumulation across stages)
+// which go straight from the accumulators to M.  Work items (k-group, xi, stage) are dealt to the
+// workgroups in contiguous, equal ranges, so U fragments are reloaded only when xi changes.
 //   WN waves split the output channels (WN*64 per workgroup), WM = 4/WN waves split the rows.
-//   CB = C/32 (fixes the registers for the U fragments), D = stages in flight.
-// The compiler's own wait-count bookkeeping merges the pipeline state at the loop header with the
-// (store-free) prologue and then waits for all but the newest stage, which defeats the prefetch.
-// The streaming loads and the stores of this kernel are therefore issued through inline assembly,
-// invisible to that bookkeeping, and waited for with explicit counts.  The hardware retires vector
-// memory operations of a wave in issue order, so "at most X outstanding" guarantees completion of
-// every operation that has at least X younger ones.
-__device__ __forceinline__ uint4v stream_load16(const void *p)
+//   CB = C/32 (fixes the registers for the U fragments).
+//
+// Waiting.  The hardware retires the vector-memory operations of a wave in issue order, and
+// `s_waitcnt vmcnt(X)` waits until at most X are outstanding; so an operation with at least X
+// younger ones is complete after the wait.  The compiler's own bookkeeping cannot express "all
+// but the newest S-2 stages" across the loop, so the streaming loads and the stores are issued
+// through inline assembly (which it does not count) and waited for with explicit counts.  Every
+// stage issues exactly NP loads and NS stores per thread, nothing conditional; the compiler's own
+// loads of U only add younger operations, which makes the explicit waits stricter, never laxer.
+// The direct loads write LDS, not registers, so nothing the compiler allocates is written behind
+// its back; their "memory" clobber keeps LDS reads from moving across them.
+__device__ __forceinline__ void stream_to_lds16(const void *gptr, unsigned lds_wave_base)
 {
-    uint4v v;
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(p) : "memory");
-    return v;
+    // lane i of the wave writes 16 bytes at LDS address lds_wave_base + 16*i (M0 = base).  M0 is a
+    // register the compiler reserves and sets itself right before each of its own uses (it has
+    // none in this kernel), so it is not listed as clobbered.
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 : : "s"(lds_wave_base), "v"(gptr) : "memory");
 }
 __device__ __forceinline__ void stream_store(float *p, float a, float b, float c, float d)
 {
@@ -176,34 +183,44 @@ __device__ __forceinline__ void stream_store(f16 *p, float a, float b, float c, 
     const half4 v = {(f16)a, (f16)b, (f16)c, (f16)d};
     asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(p), "v"(v) : "memory");
 }
-// wait until at most X vector memory operations are outstanding, and make the registers of `r`
-// depend on the wait so that no use of them is scheduled above it
-template <int X, int NP>
-__device__ __forceinline__ void stream_wait(uint4v (&r)[NP])
+template <int X>
+__device__ __forceinline__ void stream_wait()
 {
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(X) : "memory");
-#pragma unroll
-    for (int i = 0; i < NP; ++i) asm volatile("" : "+v"(r[i]));
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(X < 63 ? X : 63) : "memory");
+}
+// wait for the loads of the i-th stage of this workgroup (i counted from its first stage):
+// younger operations = (S-2) stages of loads plus the stores of the min(i, S-1) stages completed
+// since that stage was issued
+template <int I, int S, int NP, int NS>
+__device__ __forceinline__ void stream_wait_stage(int i)
+{
+    if constexpr (I == S - 1) {
+        stream_wait<(S - 2) * NP + NS * (S - 1)>();
+    } else {
+        if (i == I) stream_wait<(S - 2) * NP + NS * I>();
+        else stream_wait_stage<I + 1, S, NP, NS>(i);
+    }
 }
 
-template <int WN, int CB, int D, typename MT>
+template <int WN, int CB, int S, typename MT>
 __global__ void __launch_bounds__(256, 1)
-contract_stationary_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__restrict__ Mo,
-                           int T, int Tp, int Kp, int k_blocks, int stages_per_xi, int xi_count, int items_total)
+contract_stream_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__restrict__ Mo,
+                       int T, int Tp, int Kp, int k_blocks, int stages_per_xi, int xi_count, int items_total)
 {
     constexpr int WM = 4 / WN;
     constexpr int SR = 32 * WM;                  // rows (tiles t) per stage
     constexpr int NP = CB * SR * 4 / 256;        // 16-byte loads per thread and stage
     constexpr int NS = 8;                        // stores per thread and stage
-    constexpr int STAGE_HALVES = CB * SR * kRowHalves;
-    static_assert(NP >= 1 && (D == 1 || D == 2 || D == 4), "pipeline shape");
-    static_assert((D - 1) * (NP + NS) <= 63, "wait count must fit the 6-bit counter");
+    constexpr int STAGE_BYTES = CB * SR * 64;    // [CB][SR] rows of 32 binary16 channels
+    static_assert(NP >= 1 && S >= 3 && S * STAGE_BYTES <= 144 * 1024, "pipeline shape");
 
-    __shared__ __align__(16) f16 lds_a[2][STAGE_HALVES];
+    __shared__ __align__(1024) unsigned char ring[S * STAGE_BYTES];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
-    const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+    const int frag_row = lane & 31;
+    const unsigned ring_base = (unsigned)(size_t)((__attribute__((address_space(3))) void *)ring);
 
     // contiguous, equal share of the work items; item = ((kg * xi_count) + xi) * stages_per_xi + tb
     const int g0 = (int)((long long)items_total * blockIdx.x / gridDim.x);
@@ -211,23 +228,23 @@ contract_stationary_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V,
     if (g0 >= g1) return;
     const int per_kg = xi_count * stages_per_xi;
 
-    // per-thread pieces of a stage: piece p -> (channel block, row, 16-byte piece of the 64-byte row)
+    // Piece p = tid + 256*i of a stage sits at LDS offset 16*p: row r = p/4 of the stage
+    // ([channel block][tile] order), physical 16-byte slot p%4.  The logical slot (which 8 channels
+    // of the row) is XOR-ed with (r/4)%4, so that the 16 rows a 128-bit fragment read touches in one
+    // phase fall into 16 different bank groups.  Each lane picks the global address that belongs in
+    // its fixed LDS slot.
     int p_row[NP];
     size_t p_off[NP];
-    int p_lds[NP];
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
         const int p = tid + i * 256;
-        const int cb = p / (SR * 4);
-        p_row[i] = (p >> 2) % SR;
-        p_off[i] = (size_t)cb * T * kChanBlock + (p & 3) * 8;
-        p_lds[i] = (cb * SR + p_row[i]) * kRowHalves + (p & 3) * 8;
+        const int r = p >> 2;
+        const int cb = r / SR;
+        const int q = (p & 3) ^ ((r >> 2) & 3);
+        p_row[i] = r % SR;
+        p_off[i] = (size_t)cb * T * kChanBlock + q * 8;
     }
-
-    // Every stage issues exactly NP loads and NS stores per thread (nothing conditional), which is
-    // what the explicit wait counts below rely on.
-    uint4v regs[D][NP];
-    auto issue_stage = [&](int g, uint4v (&dst)[NP]) __attribute__((always_inline)) {
+    auto issue_stage = [&](int g, int slot) __attribute__((always_inline)) {
         if (g > g1 - 1) g = g1 - 1;                                    // tail: refetch the last stage
         const int rem = g % per_kg;
         const int xi = rem / stages_per_xi, tb = rem - xi * stages_per_xi;
@@ -235,12 +252,9 @@ contract_stationary_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V,
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
             int t = tb * SR + p_row[i]; if (t > T - 1) t = T - 1;      // rows past the end: reread the last
-            dst[i] = stream_load16(base + p_off[i] + (size_t)t * kChanBlock);
+            stream_to_lds16(base + p_off[i] + (size_t)t * kChanBlock,
+                            ring_base + slot * STAGE_BYTES + (i * 256 + wave * 64) * 16);
         }
-    };
-    auto land_stage = [&](int buf, const uint4v (&src)[NP]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < NP; ++i) *reinterpret_cast<uint4v *>(&lds_a[buf][p_lds[i]]) = src[i];
     };
 
     half8 ufrag[2][CB][2];                        // this wave's 64 output channels x all C channels of U[xi]
@@ -254,16 +268,18 @@ contract_stationary_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V,
 #pragma unroll
                 for (int kk = 0; kk < 2; ++kk)
                     ufrag[nb][cb][kk] = *reinterpret_cast<const half8 *>(
-                        U + (((size_t)xi * CB + cb) * Kp + k) * kChanBlock + kk * 16 + frag_k);
+                        U + (((size_t)xi * CB + cb) * Kp + k) * kChanBlock + kk * 16 + (lane >> 5) * 8);
         }
     };
 
-    // One work item.  YOUNGER = operations issued after the loads of stage g+1 at the point of
-    // the wait: (D-1) stages of loads, and the stores of the stages completed since.
-    auto do_stage = [&](int g, uint4v (&slot_next)[NP], uint4v (&slot_land)[NP], auto younger) __attribute__((always_inline)) {
-        constexpr int YOUNGER = decltype(younger)::value;
-        const int buf = (g - g0) & 1;
-        issue_stage(g + D, slot_next);                     // this slot was landed one item ago
+    // prologue: S-1 stages in flight
+    for (int j = 0; j < S - 1; ++j) issue_stage(g0 + j, j);
+
+    int slot = 0;
+    for (int g = g0; g < g1; ++g) {
+        stream_wait_stage<0, S, NP, NS>(g - g0);           // this wave's pieces of stage g have landed
+        __syncthreads();                                   // everyone's have; slot-1 is free again
+        issue_stage(g + S - 1, slot == 0 ? S - 1 : slot - 1);
 
         const int seg = g / stages_per_xi;                 // = kg * xi_count + xi
         const int kg = seg / xi_count, xi = seg - kg * xi_count, tb = g - seg * stages_per_xi;
@@ -280,17 +296,17 @@ contract_stationary_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V,
         for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[nb][e] = 0.0f;
+        const unsigned char *stage = ring + slot * STAGE_BYTES;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                const half8 vf = *reinterpret_cast<const half8 *>(
-                    &lds_a[buf][(cb * SR + wm * 32 + frag_row) * kRowHalves + kk * 16 + frag_k]);
+                const int r = cb * SR + wm * 32 + frag_row;
+                const int phys = (kk * 2 + (lane >> 5)) ^ ((r >> 2) & 3);
+                const half8 vf = *reinterpret_cast<const half8 *>(stage + r * 64 + phys * 16);
                 acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ufrag[0][cb][kk], vf, acc[0], 0, 0, 0);
                 acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ufrag[1][cb][kk], vf, acc[1], 0, 0, 0);
             }
-        stream_wait<YOUNGER, NP>(slot_land);
-        land_stage(buf ^ 1, slot_land);
 
         // lane holds t = lane%32 and output channels 8*(e/4) + 4*(lane/32) + e%4 of each block:
         // four consecutive channels per store; rows up to Tp exist, so no store is conditional
@@ -302,53 +318,9 @@ contract_stationary_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V,
             for (int q = 0; q < 4; ++q)
                 stream_store(dst + (size_t)nb * Tp * kChanBlock + q * 8, acc[nb][4 * q], acc[nb][4 * q + 1],
                              acc[nb][4 * q + 2], acc[nb][4 * q + 3]);
-        __syncthreads();
-    };
-
-    // prologue: D stages in flight, the first one landed (its D-1 successors are younger)
-#pragma unroll
-    for (int d = 0; d < D; ++d) issue_stage(g0 + d, regs[d]);
-    stream_wait<(D - 1) * NP, NP>(regs[0]);
-    land_stage(0, regs[0]);
-    __syncthreads();
-
-    // first D items: the stores issued so far number d * NS, not yet (D-1) * NS.  The slot indices
-    // must be compile-time constants (register arrays), hence the spelled-out sequence.
-    auto first_item = [&](auto dtag) __attribute__((always_inline)) {
-        constexpr int d = decltype(dtag)::value;
-        do_stage(g0 + d, regs[d], regs[(d + 1) % D],
-                 std::integral_constant<int, (D - 1) * NP + (d < D - 1 ? d : D - 1) * NS>{});
-    };
-    auto steady_item = [&](int g, auto dtag) __attribute__((always_inline)) {
-        constexpr int d = decltype(dtag)::value;
-        do_stage(g, regs[d], regs[(d + 1) % D], std::integral_constant<int, (D - 1) * (NP + NS)>{});
-    };
-    using std::integral_constant;
-    do {
-        first_item(integral_constant<int, 0>{});
-        if constexpr (D > 1) { if (g0 + 1 >= g1) break; first_item(integral_constant<int, 1>{}); }
-        if constexpr (D > 2) {
-            if (g0 + 2 >= g1) break; first_item(integral_constant<int, 2>{});
-            if (g0 + 3 >= g1) break; first_item(integral_constant<int, 3>{});
-        }
-    } while (false);
-    for (int base = g0 + D; base < g1; base += D) {
-        steady_item(base, integral_constant<int, 0>{});
-        if constexpr (D > 1) { if (base + 1 >= g1) break; steady_item(base + 1, integral_constant<int, 1>{}); }
-        if constexpr (D > 2) {
-            if (base + 2 >= g1) break; steady_item(base + 2, integral_constant<int, 2>{});
-            if (base + 3 >= g1) break; steady_item(base + 3, integral_constant<int, 3>{});
-        }
+        slot = slot == S - 1 ? 0 : slot + 1;
     }
-    // Surplus tail prefetches are still in flight.  Their destination registers must stay
-    // allocated until they have landed -- the compiler does not know these loads are asynchronous
-    // and would otherwise reuse the registers of values it sees as dead -- so every slot is named
-    // once more after the final wait, on every path that leaves the loops above.
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-    for (int d = 0; d < D; ++d)
-#pragma unroll
-        for (int i = 0; i < NP; ++i) asm volatile("" : : "v"(regs[d][i]));
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // surplus tail prefetches must land before the LDS is released
 }
 
 // binary32: 64 x 64 tile, 256 threads, 4 x 4 outputs per thread
@@ -409,8 +381,8 @@ static int launch_c16(const void *U, const void *V, void *Mo, const Geometry &g,
     return (int)hipGetLastError();
 }
 
-template <int WN, int CB, int D, typename MT>
-static int launch_stationary(const void *U, const void *V, void *Mo, const Geometry &g, hipStream_t stream)
+template <int WN, int CB, int S, typename MT>
+static int launch_stream(const void *U, const void *V, void *Mo, const Geometry &g, hipStream_t stream)
 {
     constexpr int SR = 32 * (4 / WN);
     static int cu_count = 0;
@@ -426,7 +398,7 @@ static int launch_stationary(const void *U, const void *V, void *Mo, const Geome
     const long long items = (long long)kgroups * g.n * g.n * stages_per_xi;
     if (items <= 0 || items > 0x7fffffffLL) return (int)hipErrorInvalidValue;
     const int blocks = (int)(items < cu_count ? items : cu_count);
-    hipLaunchKernelGGL((contract_stationary_kernel<WN, CB, D, MT>), dim3(blocks), dim3(256), 0, stream,
+    hipLaunchKernelGGL((contract_stream_kernel<WN, CB, S, MT>), dim3(blocks), dim3(256), 0, stream,
                        (const f16 *)U, (const f16 *)V, (MT *)Mo, (int)g.T, (int)g.Tp, g.Kp, g.k_blocks,
                        stages_per_xi, g.n * g.n, (int)items);
     return (int)hipGetLastError();
@@ -443,21 +415,20 @@ static int launch_c16_tiled(const void *U, const void *V, void *Mo, const Geomet
 template <typename MT>
 static int launch_c16_shape(const void *U, const void *V, void *Mo, const Geometry &g, hipStream_t s)
 {
-    // The register-staged weight-stationary kernel is switched off: its inline-asm loads are
-    // asynchronous behind the compiler's back, and under register pressure the compiler copies or
-    // reuses their destination registers while the loads are still in flight.
-    if (true) return launch_c16_tiled<MT>(U, V, Mo, g, s);
-    // weight-stationary kernel: C in {64, 128, 256} and K a multiple of the workgroup's channel span
+    // streaming kernel: C in {64, 128, 256} and K a multiple of the workgroup's channel span;
+    // ring depth S: as many stages as fit about 128 KiB of LDS, at most 8
     const int cb = g.c_blocks;
     const int wn = g.Kp % 256 == 0 ? 4 : g.Kp % 128 == 0 ? 2 : g.Kp % 64 == 0 ? 1 : 0;
-    if (wn == 4 && cb == 8) return launch_stationary<4, 8, 4, MT>(U, V, Mo, g, s);
-    if (wn == 4 && cb == 4) return launch_stationary<4, 4, 4, MT>(U, V, Mo, g, s);
-    if (wn == 4 && cb == 2) return launch_stationary<4, 2, 4, MT>(U, V, Mo, g, s);
-    if (wn == 2 && cb == 8) return launch_stationary<2, 8, 2, MT>(U, V, Mo, g, s);
-    if (wn == 2 && cb == 4) return launch_stationary<2, 4, 4, MT>(U, V, Mo, g, s);
-    if (wn == 2 && cb == 2) return launch_stationary<2, 2, 4, MT>(U, V, Mo, g, s);
-    if (wn == 1 && cb == 4) return launch_stationary<1, 4, 2, MT>(U, V, Mo, g, s);
-    if (wn == 1 && cb == 2) return launch_stationary<1, 2, 4, MT>(U, V, Mo, g, s);
+    if (kUseStreamKernel) {
+        if (wn == 4 && cb == 8) return launch_stream<4, 8, 8, MT>(U, V, Mo, g, s);   // 16 KiB stages
+        if (wn == 4 && cb == 4) return launch_stream<4, 4, 8, MT>(U, V, Mo, g, s);   //  8 KiB
+        if (wn == 4 && cb == 2) return launch_stream<4, 2, 8, MT>(U, V, Mo, g, s);   //  4 KiB
+        if (wn == 2 && cb == 8) return launch_stream<2, 8, 4, MT>(U, V, Mo, g, s);   // 32 KiB
+        if (wn == 2 && cb == 4) return launch_stream<2, 4, 8, MT>(U, V, Mo, g, s);   // 16 KiB
+        if (wn == 2 && cb == 2) return launch_stream<2, 2, 8, MT>(U, V, Mo, g, s);   //  8 KiB
+        if (wn == 1 && cb == 4) return launch_stream<1, 4, 4, MT>(U, V, Mo, g, s);   // 32 KiB
+        if (wn == 1 && cb == 2) return launch_stream<1, 2, 8, MT>(U, V, Mo, g, s);   // 16 KiB
+    }
     return launch_c16_tiled<MT>(U, V, Mo, g, s);       // other shapes: tiled kernel
 }
 
