@@ -20,11 +20,18 @@ __device__ __forceinline__ void store_from_f32(f16 *p, float v) { *p = (f16)v; }
 // fused multiply-add and the conversion into one v_fma_mixlo_f16, which rounds the exact
 // a*b+c once to binary16 and therefore disagrees, in the last place, with "round to binary32,
 // then to binary16" -- the order the input-transform contract prescribes.
-__device__ __forceinline__ void store_rounded_twice(float *p, float v) { *p = v; }
-__device__ __forceinline__ void store_rounded_twice(f16 *p, float v)
+template <typename P> __device__ __forceinline__ void store_rounded_twice(P *p, float v);
+template <> __device__ __forceinline__ void store_rounded_twice(float *p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_rounded_twice(f16 *p, float v)
 {
     asm volatile("" : "+v"(v));
     *p = (f16)v;
+}
+__device__ __forceinline__ float round_twice(float v, float *) { return v; }
+__device__ __forceinline__ f16 round_twice(float v, f16 *)
+{
+    asm volatile("" : "+v"(v));
+    return (f16)v;
 }
 
 __device__ __forceinline__ float fma32(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
@@ -42,6 +49,20 @@ __device__ __forceinline__ f16 round_f64_to(double v, f16 *)
     if (away) bits -= 1;                          // step back to the truncated magnitude
     bits |= 1u;                                   // inexact: force the last place odd
     return (f16)__uint_as_float(bits);
+}
+
+// A pointer into global memory formed as `wave-uniform base + 32-bit per-thread byte offset`.
+// The base is pinned to scalar registers and made opaque to the optimizer, so the access is
+// selected with a scalar base operand instead of per-thread 64-bit address arithmetic on the
+// vector ALU; the result is typed as a global-memory pointer so that it stays a global access.
+#define NOVA_GLOBAL __attribute__((address_space(1)))
+template <typename P>
+__device__ __forceinline__ NOVA_GLOBAL P *plane_element(P *uniform_base, unsigned byte_offset)
+{
+    unsigned long long bits = reinterpret_cast<unsigned long long>(uniform_base);
+    asm volatile("" : "+s"(bits));
+    NOVA_GLOBAL char *base = reinterpret_cast<NOVA_GLOBAL char *>(bits);
+    return reinterpret_cast<NOVA_GLOBAL P *>(base + byte_offset);
 }
 
 // blockIdx.x -> logical block id such that consecutive logical ids run on the same XCD

@@ -166,15 +166,19 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
         for (int i = 0; i < N; ++i) tmp[i][b] = o[i];
     }
 
+    // position xi lives in its own plane of V; the plane base is uniform (scalar registers), the
+    // offset inside the plane is per thread and fits 32 bits (checked by the launcher)
     const long long t = ((long long)img * tiles_h + tr) * tiles_w + tc0 + j;
     const size_t xi_stride = (size_t)c_blocks * Ttot * kChanBlock;
-    T *dst = V + ((size_t)cb * Ttot + t) * kChanBlock + c_in;
+    const unsigned in_plane = (unsigned)((((size_t)cb * Ttot + t) * kChanBlock + c_in) * sizeof(T));   // bytes
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         float o[N];
         input_transform_1d<N, SYM>(tmp[i], o, coef);
 #pragma unroll
-        for (int jj = 0; jj < N; ++jj) store_rounded_twice(dst + (size_t)(i * N + jj) * xi_stride, o[jj]);
+        for (int jj = 0; jj < N; ++jj) {
+            *plane_element(V + (size_t)(i * N + jj) * xi_stride, in_plane) = round_twice(o[jj], (T *)nullptr);
+        }
     }
 }
 
@@ -232,6 +236,7 @@ static int launch_it(const nova_transforms *t, const void *x, void *V, const Geo
     const int twb = ceil_div(g.tiles_w, sh.groups);
     const size_t lds_bytes = strip_shape<N, T>(twb, vec, sh);
     if (lds_bytes > 64 * 1024 || sh.pieces < 2) return (int)hipErrorInvalidValue;
+    if ((size_t)g.c_blocks * g.T * kChanBlock * sizeof(T) >= ((size_t)1 << 32)) return (int)hipErrorInvalidValue;
     const int threads = ((twb * 32 + 63) / 64) * 64;
     const long long blocks = (long long)sh.groups * g.tiles_h * g.c_blocks * g.N;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;

@@ -78,15 +78,17 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
     const int j = threadIdx.x >> 5, k_in = threadIdx.x & 31;
     if (j < sh.twb && tc0 + j < tiles_w) {
         const long long t = ((long long)img * tiles_h + tr) * tiles_w + tc0 + j;
+        // plane base of each xi is uniform (scalar registers); the offset inside the plane is per
+        // thread and fits 32 bits (checked by the launcher)
         const size_t xi_stride = (size_t)k_blocks * Ttot * kChanBlock;
-        const MT *src = Mp + ((size_t)kb * Ttot + t) * kChanBlock + k_in;
+        const unsigned in_plane = (unsigned)((((size_t)kb * Ttot + t) * kChanBlock + k_in) * sizeof(MT));   // bytes
 
         float z[M][N];                    // A^T M, column by column
 #pragma unroll
         for (int b = 0; b < N; ++b) {
             float v[N], o[M];
 #pragma unroll
-            for (int a = 0; a < N; ++a) v[a] = load_f32(src + (size_t)(a * N + b) * xi_stride);
+            for (int a = 0; a < N; ++a) v[a] = (float)*plane_element(Mp + (size_t)(a * N + b) * xi_stride, in_plane);
             output_transform_1d<N, SYM>(v, o, coef);
 #pragma unroll
             for (int p = 0; p < M; ++p) z[p][b] = o[p];
@@ -178,6 +180,7 @@ static int launch_ot(const nova_transforms *t, const void *Mp, void *y, const Ge
     const int twb = ceil_div(g.tiles_w, sh.groups);
     const size_t lds_bytes = out_shape<N, T>(twb, sh);
     if (lds_bytes > 64 * 1024) return (int)hipErrorInvalidValue;
+    if ((size_t)g.k_blocks * g.Tp * kChanBlock * sizeof(MT) >= ((size_t)1 << 32)) return (int)hipErrorInvalidValue;
     const bool vec = g.W % PE == 0 && ((uintptr_t)y % 16) == 0 && (sh.groups == 1 || (twb * M) % PE == 0);
     const int threads = ((twb * 32 + 63) / 64) * 64;
     const long long blocks = (long long)sh.groups * g.tiles_h * g.k_blocks * g.N;

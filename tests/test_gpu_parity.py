@@ -277,3 +277,48 @@ def test_vgg_conv3_full_size_sampled_images():
             bad, bad_o = ~np.isfinite(y), ~np.isfinite(y_o)
             say(f"  non-finite outputs: gpu {bad.mean():.3f} oracle {bad_o.mean():.3f}")
             assert bad_o.mean() > 0.9 and (bad == bad_o).mean() > 0.99
+
+
+def test_resnet_shapes_reduced_batch():
+    # the four ResNet-50-style stride-1 3x3 shapes (C = K = 64 @56, 128 @28, 256 @14, 512 @7), F(8,3)
+    # with NOVA points, at batch 4 instead of 256; 14x14 and 7x7 need cropped (padded) tiles
+    points = synth.point_set("nova", 8)
+    t = nova.nova_make_transforms(points, 8, 3)
+    for idx, (ch, hw) in enumerate(synth.RESNET_SHAPES):
+        say(f"[case] ResNet-style shape C=K={ch} H=W={hw}, batch 4")
+        x, w = synth.make_layer(4, ch, ch, hw, hw, seed=5000 + idx, dtype="f16")
+        xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+        U = nova.nova_filter_transform(t, wd)
+        y = nova.nova_winograd_conv2d(t, xd, U, ch).cpu().numpy().astype(np.float64)
+        y_o = conv.winograd_conv2d_emulated(x.astype(np.float64), w.astype(np.float64), pts(points), 8, storage=16)
+        err = rel_l2(y, y_o)
+        say(f"  rel-L2 vs emulation {err:.3e}")
+        assert np.isfinite(y).all() and err < 5e-3
+
+
+@pytest.mark.parametrize("m", [6, 8])
+def test_vgg_stack_reduced_size(m):
+    # the 13-layer VGG-16 conv stack (ReLU fused, 2x2 max-pool after layers 2, 4, 7, 10, 13) on a
+    # 2 x 3 x 32 x 32 input; every layer is checked on its own: the oracle is fed the GPU's input to
+    # that layer, so rounding differences do not accumulate through the stack
+    points = synth.point_set("nova", m)
+    t = nova.nova_make_transforms(points, m, 3)
+    rng = np.random.default_rng(4000 + m)
+    act = torch.from_numpy(rng.standard_normal((2, 3, 32, 32)).astype(np.float16)).to(DEV)
+    for layer, (cin, cout) in enumerate(synth.VGG16_LAYERS, start=1):
+        w = (rng.standard_normal((cout, cin, 3, 3)) * np.sqrt(2.0 / (9.0 * cin))).astype(np.float16)
+        say(f"[case] VGG stack F({m},3) layer {layer}: {cin}->{cout} @ {act.shape[2]}x{act.shape[3]}")
+        U = nova.nova_filter_transform(t, torch.from_numpy(w).to(DEV))
+        y = nova.nova_winograd_conv2d(t, act, U, cout, flags=nova.NOVA_FLAG_RELU)
+        x64 = act.cpu().numpy().astype(np.float64)
+        y_o = conv.winograd_conv2d_emulated(x64, w.astype(np.float64), pts(points), m, storage=16, relu=True)
+        got = y.cpu().numpy().astype(np.float64)
+        err = rel_l2(got, y_o)
+        say(f"  rel-L2 vs emulation {err:.3e}")
+        assert np.isfinite(got).all() and err < 5e-3
+        if layer in synth.VGG16_POOL_AFTER:
+            pooled = nova.nova_relu_maxpool2x2(y)
+            assert np.array_equal(pooled.cpu().numpy().astype(np.float64), conv.relu_maxpool2x2(got))
+            act = pooled
+        else:
+            act = y
