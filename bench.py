@@ -22,6 +22,16 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the
+# same counters read for a plain 256 MiB copy (FETCH_SIZE x 1.9998, WRITE_SIZE x 1.0000); see
+# profiles/vgg_conv3_f83_fp16_hbm_traffic.txt.  Keyed by (workload, points, products dtype,
+# images per slab, stage); anything not measured reports null.
+MEASURED_TRAFFIC_BYTES = {
+    ("vgg_conv3_f83_fp16", "nova", "f32", 32, "input_transform"): 132473256,
+    ("vgg_conv3_f83_fp16", "nova", "f32", 32, "contract"): 266075716,
+    ("vgg_conv3_f83_fp16", "nova", "f32", 32, "output_transform"): 212103481,
+}
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -33,6 +43,8 @@ def main():
     ap.add_argument("--images-per-slab", type=int, default=0, help="0 = library default")
     ap.add_argument("--m-f16", action="store_true", help="keep the products M in fp16 (NOVA_FLAG_M_F16)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg (profiling runs)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy, the yardstick for rocprofv3's FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards by batch with no exchange; "
@@ -126,9 +138,18 @@ def main():
         st["hbm_frac"] = st["gbs"] / HBM_PEAK_GBS
     dominant = max(stages, key=lambda k: stages[k]["us"])
     dom = stages[dominant]
+    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, args.points, "f16" if m_es == 2 else "f32",
+                                          int(slab_imgs), dominant))
     roofline = dict(kernel=dominant, bound="hbm", achieved=round(dom["gbs"], 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(dom["gbs"] / HBM_PEAK_GBS, 4), traffic=None,
+                    frac=round(dom["gbs"] / HBM_PEAK_GBS, 4), traffic=traffic,
                     launch_us=round(dom["us"], 2), algorithmic_bytes=dom["bytes"])
+
+    if args.copy_calibration:
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     # ---- accuracy on sampled images and the CPU oracle leg
     result_extra = {}

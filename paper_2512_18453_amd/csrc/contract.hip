@@ -20,7 +20,7 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 
-constexpr bool kUseStreamKernel = false;   // until the direct global->LDS load is validated on the device
+constexpr bool kUseStreamKernel = true;
 constexpr int kRowHalves = 40;   // LDS row pitch of a 32-channel operand row, in binary16 units (80 B)
 
 template <int BM, int BN, int WM, int WN, typename MT>
@@ -223,8 +223,11 @@ contract_stream_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT 
     const unsigned ring_base = (unsigned)(size_t)((__attribute__((address_space(3))) void *)ring);
 
     // contiguous, equal share of the work items; item = ((kg * xi_count) + xi) * stages_per_xi + tb
-    const int g0 = (int)((long long)items_total * blockIdx.x / gridDim.x);
-    const int g1 = (int)((long long)items_total * (blockIdx.x + 1) / gridDim.x);
+    // (workgroups that are neighbours in this order run on the same XCD, so the U[xi] slice that
+    // two or three of them share is fetched into one L2 only)
+    const unsigned wg = xcd_local_block_id(blockIdx.x, gridDim.x);
+    const int g0 = (int)((long long)items_total * wg / gridDim.x);
+    const int g1 = (int)((long long)items_total * (wg + 1) / gridDim.x);
     if (g0 >= g1) return;
     const int per_kg = xi_count * stages_per_xi;
 
@@ -245,15 +248,18 @@ contract_stream_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT 
         p_off[i] = (size_t)cb * T * kChanBlock + q * 8;
     }
     auto issue_stage = [&](int g, int slot) __attribute__((always_inline)) {
-        if (g > g1 - 1) g = g1 - 1;                                    // tail: refetch the last stage
+        // past the end of the range the loads are still issued (the wait counts assume a fixed
+        // number per stage) but all lanes read the first 16 bytes of V: one cached request
+        const bool surplus = g > g1 - 1;
+        if (surplus) g = g1 - 1;
         const int rem = g % per_kg;
         const int xi = rem / stages_per_xi, tb = rem - xi * stages_per_xi;
         const f16 *base = V + (size_t)xi * CB * T * kChanBlock;
 #pragma unroll
         for (int i = 0; i < NP; ++i) {
             int t = tb * SR + p_row[i]; if (t > T - 1) t = T - 1;      // rows past the end: reread the last
-            stream_to_lds16(base + p_off[i] + (size_t)t * kChanBlock,
-                            ring_base + slot * STAGE_BYTES + (i * 256 + wave * 64) * 16);
+            const f16 *src = surplus ? V : base + p_off[i] + (size_t)t * kChanBlock;
+            stream_to_lds16(src, ring_base + slot * STAGE_BYTES + (i * 256 + wave * 64) * 16);
         }
     };
 

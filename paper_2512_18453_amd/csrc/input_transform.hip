@@ -99,7 +99,7 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
         // the image.  All loads of a round are issued before the first LDS write waits on them.
         w_al = (w_lo + PE) / PE * PE - PE;        // floor to a multiple of PE (w_lo >= -1)
         const int slots = kChanBlock * N * sh.pieces;
-        constexpr int R = 4;
+        constexpr int R = 12;                     // usually the whole strip in one round trip
         for (int base = threadIdx.x; base < slots; base += R * (int)blockDim.x) {
             u32x4 val[R];
             int dst[R];

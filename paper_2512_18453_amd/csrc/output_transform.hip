@@ -55,10 +55,10 @@ struct OutShape {
     int k_pitch;      // LDS elements per channel
 };
 
-template <int N, typename T, typename MT, bool SYM, bool VEC>
+template <int N, typename T, typename MT, bool SYM, bool VEC, bool RELU>
 __global__ void __launch_bounds__(512)
 output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int H, int W,
-                        int tiles_h, int tiles_w, int k_blocks, long long Ttot, OutShape sh, int relu,
+                        int tiles_h, int tiles_w, int k_blocks, long long Ttot, OutShape sh,
                         OutCoef<N> coef)
 {
     constexpr int M = N - 2;
@@ -101,7 +101,7 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
 #pragma unroll
             for (int q = 0; q < M; ++q) {
                 float val = o[q];
-                if (relu) val = val < 0.0f ? 0.0f : val;      // NaN stays NaN
+                if constexpr (RELU) val = val < 0.0f ? 0.0f : val;      // NaN stays NaN
                 store_from_f32(dst + p * sh.cols_pitch + q, val);
             }
         }
@@ -185,12 +185,17 @@ static int launch_ot(const nova_transforms *t, const void *Mp, void *y, const Ge
     const int threads = ((twb * 32 + 63) / 64) * 64;
     const long long blocks = (long long)sh.groups * g.tiles_h * g.k_blocks * g.N;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
-    void (*kern)(const MT *, T *, int, int, int, int, int, int, long long, OutShape, int, OutCoef<N>);
-    if (t->symmetric) kern = vec ? output_transform_kernel<N, T, MT, true, true> : output_transform_kernel<N, T, MT, true, false>;
-    else              kern = vec ? output_transform_kernel<N, T, MT, false, true> : output_transform_kernel<N, T, MT, false, false>;
+    void (*kern)(const MT *, T *, int, int, int, int, int, int, long long, OutShape, OutCoef<N>);
+    const bool relu = (flags & NOVA_FLAG_RELU) != 0;
+    if (t->symmetric) {
+        if (vec) kern = relu ? output_transform_kernel<N, T, MT, true, true, true> : output_transform_kernel<N, T, MT, true, true, false>;
+        else     kern = relu ? output_transform_kernel<N, T, MT, true, false, true> : output_transform_kernel<N, T, MT, true, false, false>;
+    } else {
+        if (vec) kern = relu ? output_transform_kernel<N, T, MT, false, true, true> : output_transform_kernel<N, T, MT, false, true, false>;
+        else     kern = relu ? output_transform_kernel<N, T, MT, false, false, true> : output_transform_kernel<N, T, MT, false, false, false>;
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds_bytes, stream,
-                       (const MT *)Mp, (T *)y, g.K, g.H, g.W, g.tiles_h, g.tiles_w, g.k_blocks, g.Tp, sh,
-                       (flags & NOVA_FLAG_RELU) ? 1 : 0, coef);
+                       (const MT *)Mp, (T *)y, g.K, g.H, g.W, g.tiles_h, g.tiles_w, g.k_blocks, g.Tp, sh, coef);
     return (int)hipGetLastError();
 }
 
