@@ -16,6 +16,18 @@
 
 namespace nova {
 
+int device_cu_count()
+{
+    static int cached[64] = {};
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
@@ -391,14 +403,7 @@ template <int WN, int CB, int S, typename MT>
 static int launch_stream(const void *U, const void *V, void *Mo, const Geometry &g, hipStream_t stream)
 {
     constexpr int SR = 32 * (4 / WN);
-    static int cu_count = 0;
-    if (cu_count == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            n = 256;
-        cu_count = n;
-    }
+    const int cu_count = device_cu_count();
     const int stages_per_xi = ceil_div((int)g.T, SR);
     const int kgroups = g.Kp / (WN * 64);
     const long long items = (long long)kgroups * g.n * g.n * stages_per_xi;

@@ -19,41 +19,53 @@
 
 namespace nova {
 
-template <int N, bool SYM>
-__device__ __forceinline__ void input_transform_1d(const float (&v)[N], float (&out)[N], const InCoef<N> &k)
+// Rows [LO, HI) of one 1D transform: out[p - LO] = sum_a B^T[p][a] v[a] in the contracted order.
+// With SYM the range must not cut a (+a, -a) pair of rows (rows 2q+1, 2q+2).
+template <int N, bool SYM, int LO, int HI>
+__device__ __forceinline__ void input_transform_rows(const float (&v)[N], float (&out)[HI - LO], const InCoef<N> &k)
 {
     constexpr int H = (N - 2) / 2;
     if constexpr (SYM) {
-        float e0 = 0.0f;
+        if constexpr (LO == 0) {
+            float e0 = 0.0f;
 #pragma unroll
-        for (int q = 0; q <= H; ++q) e0 = fma32(k.zero[q], v[2 * q], e0);
-        out[0] = e0;
+            for (int q = 0; q <= H; ++q) e0 = fma32(k.zero[q], v[2 * q], e0);
+            out[0] = e0;
+        }
 #pragma unroll
         for (int j = 0; j < H; ++j) {
-            float E = 0.0f, O = 0.0f;
+            if (2 * j + 1 >= LO && 2 * j + 2 < HI) {
+                float E = 0.0f, O = 0.0f;
 #pragma unroll
-            for (int q = 0; q < H; ++q) E = fma32(k.ev[j * H + q], v[2 * q + 2], E);
+                for (int q = 0; q < H; ++q) E = fma32(k.ev[j * H + q], v[2 * q + 2], E);
 #pragma unroll
-            for (int q = 0; q < H; ++q) O = fma32(k.od[j * H + q], v[2 * q + 1], O);
-            out[2 * j + 1] = E + O;
-            out[2 * j + 2] = E - O;
+                for (int q = 0; q < H; ++q) O = fma32(k.od[j * H + q], v[2 * q + 1], O);
+                out[2 * j + 1 - LO] = E + O;
+                out[2 * j + 2 - LO] = E - O;
+            }
         }
-        float oi = 0.0f;
+        if constexpr (HI == N) {
+            float oi = 0.0f;
 #pragma unroll
-        for (int q = 0; q <= H; ++q) oi = fma32(k.inf[q], v[2 * q + 1], oi);
-        out[N - 1] = oi;
+            for (int q = 0; q <= H; ++q) oi = fma32(k.inf[q], v[2 * q + 1], oi);
+            out[N - 1 - LO] = oi;
+        }
     } else {
 #pragma unroll
-        for (int p = 0; p < N; ++p) {
+        for (int p = LO; p < HI; ++p) {
             float E = 0.0f, O = 0.0f;
 #pragma unroll
             for (int a = 0; a < N; a += 2) E = fma32(k.bt[p * N + a], v[a], E);
 #pragma unroll
             for (int a = 1; a < N; a += 2) O = fma32(k.bt[p * N + a], v[a], O);
-            out[p] = E + O;
+            out[p - LO] = E + O;
         }
     }
 }
+
+// Where the rows are split between the two waves that share a tile pair: half 0 takes rows
+// [0, SP), half 1 rows [SP, N); SP is odd so that no (+a, -a) pair of rows is cut.
+template <int N> struct RowSplit { static constexpr int value = ((N / 2) % 2 == 1) ? N / 2 : N / 2 + 1; };
 
 // LDS strip: [32 channels][N rows][row_pitch columns], columns fastest (the order of x in
 // memory, so staging moves 16-byte pieces); strip column lc holds image column w_al + lc, where
@@ -69,6 +81,56 @@ struct StripShape {
     unsigned piece_magic;   // ceil(2^32 / pieces): s / pieces == mulhi(s, magic) while s * pieces < 2^32
 };
 
+template <int N, typename T, bool SYM, bool ALIGNED, int LO, int HI>
+__device__ __forceinline__ void transform_rows_of_tile(const T *tile, int row_pitch, T *mine, int xi_pitch,
+                                                       const InCoef<N> &coef)
+{
+    // columns of the tile first: tmp[i - LO][b] = sum_a B^T[i][a] d[a][b] for this wave's rows i
+    float tmp[HI - LO][N];
+    T win[N][N];                                  // the tile window d[a][b] in storage format
+    if constexpr (ALIGNED) {
+        // m = 8 and a strip whose column 0 is a multiple of 8: columns 1..8 of every window row are
+        // one aligned 16-byte (fp16) or two aligned 16-byte (fp32) reads; an unaligned wide LDS read
+        // costs several passes
+        constexpr int PE = 16 / (int)sizeof(T);
+        typedef T vecT __attribute__((ext_vector_type(PE)));
+#pragma unroll
+        for (int a = 0; a < N; ++a) {
+            const T *row = tile + a * row_pitch;
+            win[a][0] = row[0];
+#pragma unroll
+            for (int v = 0; v < 8 / PE; ++v) {
+                const vecT piece = *reinterpret_cast<const vecT *>(__builtin_assume_aligned(row + 1 + v * PE, 16));
+#pragma unroll
+                for (int e = 0; e < PE; ++e) win[a][1 + v * PE + e] = piece[e];
+            }
+            win[a][9] = row[9];
+        }
+    } else {
+#pragma unroll
+        for (int a = 0; a < N; ++a)
+#pragma unroll
+            for (int b = 0; b < N; ++b) win[a][b] = tile[a * row_pitch + b];
+    }
+#pragma unroll
+    for (int b = 0; b < N; ++b) {
+        float d[N], o[HI - LO];
+#pragma unroll
+        for (int a = 0; a < N; ++a) d[a] = (float)win[a][b];
+        input_transform_rows<N, SYM, LO, HI>(d, o, coef);
+#pragma unroll
+        for (int i = 0; i < HI - LO; ++i) tmp[i][b] = o[i];
+    }
+    // then along each of those rows: V[i][j] = sum_b tmp[i][b] B^T[j][b], rounded to storage
+#pragma unroll
+    for (int i = LO; i < HI; ++i) {
+        float o[N];
+        input_transform_rows<N, SYM, 0, N>(tmp[i - LO], o, coef);
+#pragma unroll
+        for (int jj = 0; jj < N; ++jj) mine[((i - LO) * N + jj) * xi_pitch] = round_twice(o[jj], (T *)nullptr);
+    }
+}
+
 template <int N, typename T, bool SYM, bool VEC>
 __global__ void __launch_bounds__(512)
 input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H, int W,
@@ -77,6 +139,7 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
 {
     constexpr int M = N - 2;
     constexpr int PE = 16 / (int)sizeof(T);      // elements per 16-byte piece
+    constexpr int SP = RowSplit<N>::value;
     typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -94,12 +157,13 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
     const int w_lo = tc0 * M - 1;         // first image column the group needs
     int w_al = w_lo;                      // image column of strip column 0
 
+    // ---- stage the strip [32 channels][N rows][columns] in the order it has in memory
     if constexpr (VEC) {
         // W is a multiple of PE and x is 16-byte aligned: every piece is wholly inside or outside
         // the image.  All loads of a round are issued before the first LDS write waits on them.
         w_al = (w_lo + PE) / PE * PE - PE;        // floor to a multiple of PE (w_lo >= -1)
         const int slots = kChanBlock * N * sh.pieces;
-        constexpr int R = 12;                     // usually the whole strip in one round trip
+        constexpr int R = 8;                      // usually the whole strip in one round trip
         for (int base = threadIdx.x; base < slots; base += R * (int)blockDim.x) {
             u32x4 val[R];
             int dst[R];
@@ -150,34 +214,46 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
     }
     __syncthreads();
 
-    // ---- transform: thread = (tile j of the group, channel c_in)
-    const int j = threadIdx.x >> 5, c_in = threadIdx.x & 31;
-    if (j >= sh.twb || tc0 + j >= tiles_w) return;
-
+    // ---- transform.  Waves come in pairs that share two tiles: lane = (tile of the pair, channel),
+    // and the two waves of a pair take the transform rows [0, SP) and [SP, N) -- half the registers
+    // per thread, twice the waves, and no work done twice (the rows of a 1D transform are
+    // independent once no +a/-a pair is cut).  The results are collected in registers first ...
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int j = (wave >> 1) * 2 + (lane >> 5), c_in = lane & 31, half = wave & 1;
+    const bool active = j < sh.twb && tc0 + j < tiles_w;
     const T *tile = lds + c_in * sh.ch_pitch + (w_lo - w_al) + j * M;
-    float tmp[N][N];
-#pragma unroll
-    for (int b = 0; b < N; ++b) {
-        float d[N], o[N];
-#pragma unroll
-        for (int a = 0; a < N; ++a) d[a] = load_f32(tile + a * sh.row_pitch + b);
-        input_transform_1d<N, SYM>(d, o, coef);
-#pragma unroll
-        for (int i = 0; i < N; ++i) tmp[i][b] = o[i];
+    constexpr int ROWS_MAX = SP > N - SP ? SP : N - SP;
+    T res[ROWS_MAX * N];
+    if (active) {
+        constexpr bool AL = VEC && N == 10;       // window column 1 = image column 8*(tc0+j): 16-byte aligned
+        if (half == 0) transform_rows_of_tile<N, T, SYM, AL, 0, SP>(tile, sh.row_pitch, res, 1, coef);
+        else           transform_rows_of_tile<N, T, SYM, AL, SP, N>(tile, sh.row_pitch, res, 1, coef);
     }
+    __syncthreads();                          // the strip has been read; its LDS is reused below
 
-    // position xi lives in its own plane of V; the plane base is uniform (scalar registers), the
-    // offset inside the plane is per thread and fits 32 bits (checked by the launcher)
-    const long long t = ((long long)img * tiles_h + tr) * tiles_w + tc0 + j;
-    const size_t xi_stride = (size_t)c_blocks * Ttot * kChanBlock;
-    const unsigned in_plane = (unsigned)((((size_t)cb * Ttot + t) * kChanBlock + c_in) * sizeof(T));   // bytes
+    // ... and go back through LDS as [xi][tile of the group][32 channels], so that they leave in
+    // 16-byte stores (2-byte stores, one per lane and position, are what limits this kernel
+    // otherwise): for one xi the tiles of the group are adjacent in V, twb*64 contiguous bytes.
+    if (active) {
+        T *mine = lds + j * kChanBlock + c_in;
+        const int first = half == 0 ? 0 : SP * N, count = half == 0 ? SP * N : (N - SP) * N;
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
-        float o[N];
-        input_transform_1d<N, SYM>(tmp[i], o, coef);
-#pragma unroll
-        for (int jj = 0; jj < N; ++jj) {
-            *plane_element(V + (size_t)(i * N + jj) * xi_stride, in_plane) = round_twice(o[jj], (T *)nullptr);
+        for (int e = 0; e < ROWS_MAX * N; ++e)
+            if (e < count) mine[(first + e) * sh.twb * kChanBlock] = res[e];
+    }
+    __syncthreads();
+    {
+        constexpr int PPR = kChanBlock / PE;               // 16-byte pieces per (xi, tile) row
+        int valid = tiles_w - tc0; if (valid > sh.twb) valid = sh.twb; if (valid < 0) valid = 0;
+        const long long t0 = ((long long)img * tiles_h + tr) * tiles_w + tc0;
+        const size_t in_plane = ((size_t)cb * Ttot + t0) * kChanBlock;
+        const size_t xi_stride = (size_t)c_blocks * Ttot * kChanBlock;
+        const int n_waves = (int)blockDim.x >> 6;
+        for (int xi = wave; xi < N * N; xi += n_waves) {
+            T *plane = V + (size_t)xi * xi_stride + in_plane;
+            const T *rows = lds + xi * sh.twb * kChanBlock;
+            for (int l = lane; l < valid * PPR; l += 64)
+                *reinterpret_cast<u32x4 *>(plane + l * PE) = *reinterpret_cast<const u32x4 *>(rows + l * PE);
         }
     }
 }
@@ -213,8 +289,11 @@ static size_t strip_shape(int twb, bool vec, StripShape &sh)
         sh.pieces = need;
         sh.row_pitch = (need + 3) / 4 * 4;
     }
-    int chp = N * sh.row_pitch;                         // multiple of 4
-    if ((chp / 4) % 2 == 0) chp += 4;                   // 4 * odd
+    // channel pitch: an odd multiple of 16 bytes on the vector path (aligned 128-bit reads, and the
+    // 16 lanes of one read phase cover all 64 banks), else 4 * odd elements
+    const int unit = vec ? 16 / (int)sizeof(T) : 4;
+    int chp = (N * sh.row_pitch + unit - 1) / unit * unit;
+    if ((chp / unit) % 2 == 0) chp += unit;
     sh.ch_pitch = chp;
     sh.twb = twb;
     sh.piece_magic = (unsigned)((((unsigned long long)1 << 32) + sh.pieces - 1) / sh.pieces);
@@ -228,16 +307,21 @@ static int launch_it(const nova_transforms *t, const void *x, void *V, const Geo
     InCoef<N> coef;
     fill_in_coef<N>(t, coef);
     const bool vec = g.W % PE == 0 && ((uintptr_t)x % 16) == 0;
-    // tiles per group: at most 16 (512 threads) and an LDS strip of at most 64 KiB
+    // tiles per group: at most 8 (two waves per tile pair, 512 threads); the LDS block holds first
+    // the strip, then the results [xi][tile][32], and may take at most 64 KiB
     StripShape sh;
-    int twb_max = 16;
-    while (twb_max > 1 && strip_shape<N, T>(twb_max, vec, sh) > 64 * 1024) --twb_max;
+    auto lds_need = [&](int twb) {
+        const size_t strip = strip_shape<N, T>(twb, vec, sh);
+        const size_t out_stage = (size_t)N * N * twb * kChanBlock * sizeof(T);
+        return strip > out_stage ? strip : out_stage;
+    };
+    int twb_max = 8;
+    while (twb_max > 1 && lds_need(twb_max) > 64 * 1024) --twb_max;
     sh.groups = ceil_div(g.tiles_w, twb_max);
     const int twb = ceil_div(g.tiles_w, sh.groups);
-    const size_t lds_bytes = strip_shape<N, T>(twb, vec, sh);
+    const size_t lds_bytes = lds_need(twb);
     if (lds_bytes > 64 * 1024 || sh.pieces < 2) return (int)hipErrorInvalidValue;
-    if ((size_t)g.c_blocks * g.T * kChanBlock * sizeof(T) >= ((size_t)1 << 32)) return (int)hipErrorInvalidValue;
-    const int threads = ((twb * 32 + 63) / 64) * 64;
+    const int threads = ((twb + 1) / 2) * 128;           // a pair of waves per pair of tiles
     const long long blocks = (long long)sh.groups * g.tiles_h * g.c_blocks * g.N;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
     void (*kern)(const T *, T *, int, int, int, int, int, int, long long, StripShape, InCoef<N>);

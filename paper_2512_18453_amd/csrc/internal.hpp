@@ -87,6 +87,7 @@ struct nova_transforms {
 // ---- kernel launchers (defined in the .hip files); all return a hipError_t as int ----
 namespace nova {
 void set_last_hip_error(int err);
+int device_cu_count();          // compute units of the current device (256 if the query fails)
 
 int launch_filter_transform(const nova_transforms *t, const void *w, int K, int C, int dtype,
                             void *U, void *stream);
