@@ -156,15 +156,20 @@ contract_f16_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__
 //
 // The contraction is bound by HBM traffic (V in, M out), not by the matrix cores, and a tiled
 // GEMM that reloads U and V per output tile is held back by load latency: it never has enough
-// bytes in flight.  Here a persistent workgroup (one per CU) keeps its slice of U[xi] -- 64
-// output channels x all C input channels per wave -- in VGPRs as ready-made MFMA fragments, and
-// streams V exactly once through a ring of S stages in LDS, filled by direct global->LDS loads
-// (no destination registers), S-1 stages in flight.  A stage is SR = 32*WM consecutive tiles t
-// with all C channels, so each stage yields finished outputs (no accumulation across stages)
-// which go straight from the accumulators to M.  Work items (k-group, xi, stage) are dealt to the
-// workgroups in contiguous, equal ranges, so U fragments are reloaded only when xi changes.
-//   WN waves split the output channels (WN*64 per workgroup), WM = 4/WN waves split the rows.
+// bytes in flight.  Here a workgroup keeps its slice of U[xi] -- NB*32 output channels x all C
+// input channels per wave -- in VGPRs as ready-made MFMA fragments, and streams its share of
+// V[xi] exactly once through a ring of S stages in LDS, filled by direct global->LDS loads (no
+// destination registers), S-1 stages in flight.  A stage is SR = 32*WM consecutive tiles t with
+// all C channels, so each stage yields finished outputs (no accumulation across stages) which go
+// straight from the accumulators to M.  A segment = all stages of one (k-group, xi): the unit
+// that shares one set of U fragments.  The grid is sized to what is resident at once (OCC
+// workgroups per CU); if that is at least the number of segments, each segment is split among
+// several workgroups and nobody reloads U, otherwise each workgroup takes a contiguous, equal
+// share of all stages and walks through it segment by segment.
+//   WN x WM waves; WN split the output channels, WM the rows of a stage.
 //   CB = C/32 (fixes the registers for the U fragments).
+// Two workgroups per CU where registers and LDS allow: the stores throttle the wave that issues
+// them when HBM writes back up, and a second workgroup's MFMAs and loads fill those gaps.
 //
 // Waiting.  The hardware retires the vector-memory operations of a wave in issue order, and
 // `s_waitcnt vmcnt(X)` waits until at most X are outstanding; so an operation with at least X
@@ -172,28 +177,32 @@ contract_f16_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__
 // but the newest S-2 stages" across the loop, so the streaming loads and the stores are issued
 // through inline assembly (which it does not count) and waited for with explicit counts.  Every
 // stage issues exactly NP loads and NS stores per thread, nothing conditional; the compiler's own
-// loads of U only add younger operations, which makes the explicit waits stricter, never laxer.
+// loads of U are complete before the loop over stages starts.
 // The direct loads write LDS, not registers, so nothing the compiler allocates is written behind
 // its back; their "memory" clobber keeps LDS reads from moving across them.
-__device__ __forceinline__ void stream_to_lds16(const void *gptr, unsigned lds_wave_base)
+// Addresses are `uniform 64-bit base (scalar registers) + 32-bit per-lane byte offset`: one VGPR
+// per access instead of two, which this kernel's register budget needs.
+__device__ __forceinline__ void stream_to_lds16(const void *uniform_base, unsigned byte_offset, unsigned lds_wave_base)
 {
     // lane i of the wave writes 16 bytes at LDS address lds_wave_base + 16*i (M0 = base).  M0 is a
     // register the compiler reserves and sets itself right before each of its own uses (it has
     // none in this kernel), so it is not listed as clobbered.
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 : : "s"(lds_wave_base), "v"(gptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 : : "s"(lds_wave_base), "v"(byte_offset), "s"(uniform_base) : "memory");
 }
-__device__ __forceinline__ void stream_store(float *p, float a, float b, float c, float d)
+template <int IMM>
+__device__ __forceinline__ void stream_store(float *uniform_base, unsigned byte_offset, float a, float b, float c, float d)
 {
     typedef float float4v __attribute__((ext_vector_type(4)));
     const float4v v = {a, b, c, d};
-    asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, %2 offset:%3" : : "v"(byte_offset), "v"(v), "s"(uniform_base), "n"(IMM) : "memory");
 }
-__device__ __forceinline__ void stream_store(f16 *p, float a, float b, float c, float d)
+template <int IMM>
+__device__ __forceinline__ void stream_store(f16 *uniform_base, unsigned byte_offset, float a, float b, float c, float d)
 {
     typedef _Float16 half4 __attribute__((ext_vector_type(4)));
     const half4 v = {(f16)a, (f16)b, (f16)c, (f16)d};
-    asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(p), "v"(v) : "memory");
+    asm volatile("global_store_dwordx2 %0, %1, %2 offset:%3" : : "v"(byte_offset), "v"(v), "s"(uniform_base), "n"(IMM) : "memory");
 }
 template <int X>
 __device__ __forceinline__ void stream_wait()
@@ -214,17 +223,24 @@ __device__ __forceinline__ void stream_wait_stage(int i)
     }
 }
 
-template <int WN, int CB, int S, typename MT>
-__global__ void __launch_bounds__(256, 1)
+// WN x WM waves: WN split the output channels (NB blocks of 32 each, so WN*NB*32 per workgroup),
+// WM split the rows of a stage (SR = 32*WM tiles).  OCC = workgroups per CU the registers and the
+// LDS ring are budgeted for: with two, one workgroup's MFMAs overlap the other's stores, which
+// throttle the issuing wave when HBM writes back up.
+template <int WN, int WM, int NB, int CB, int S, int OCC, typename MT>
+// (the second launch bound is waves per SIMD: a workgroup puts WN*WM/4 on each)
+__global__ void __launch_bounds__(64 * WN * WM, OCC * WN * WM / 4)
 contract_stream_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__restrict__ Mo,
-                       int T, int Tp, int Kp, int k_blocks, int stages_per_xi, int xi_count, int items_total)
+                       int T, int Tp, int Kp, int k_blocks, int stages_per_xi, int xi_count, int items_total, int wgs_per_seg)
 {
-    constexpr int WM = 4 / WN;
-    constexpr int SR = 32 * WM;                  // rows (tiles t) per stage
-    constexpr int NP = CB * SR * 4 / 256;        // 16-byte loads per thread and stage
-    constexpr int NS = 8;                        // stores per thread and stage
-    constexpr int STAGE_BYTES = CB * SR * 64;    // [CB][SR] rows of 32 binary16 channels
-    static_assert(NP >= 1 && S >= 3 && S * STAGE_BYTES <= 144 * 1024, "pipeline shape");
+    constexpr int THREADS = 64 * WN * WM;
+    constexpr int SR = 32 * WM;                      // rows (tiles t) per stage
+    constexpr int NP = CB * SR * 4 / THREADS;        // 16-byte loads per thread and stage
+    constexpr int NS = 4 * NB;                       // stores per thread and stage
+    constexpr int STAGE_BYTES = CB * SR * 64;        // [CB][SR] rows of 32 binary16 channels
+    static_assert(NP >= 1 && NP * THREADS == CB * SR * 4 && S >= 3 && S * STAGE_BYTES * OCC <= 144 * 1024,
+                  "pipeline shape");
+    static_assert(THREADS / 4 % 16 == 0, "the swizzle term (r/4)%4 must not depend on the piece index i");
 
     __shared__ __align__(1024) unsigned char ring[S * STAGE_BYTES];
 
@@ -234,111 +250,140 @@ contract_stream_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT 
     const int frag_row = lane & 31;
     const unsigned ring_base = (unsigned)(size_t)((__attribute__((address_space(3))) void *)ring);
 
-    // contiguous, equal share of the work items; item = ((kg * xi_count) + xi) * stages_per_xi + tb
-    // (workgroups that are neighbours in this order run on the same XCD, so the U[xi] slice that
-    // two or three of them share is fetched into one L2 only)
+    // Work items: item = ((kg * xi_count) + xi) * stages_per_xi + tb; a run of stages_per_xi items
+    // with the same (kg, xi) is a segment and needs one load of U fragments.  If there are at least
+    // as many workgroups as segments, wgs_per_seg of them share each segment and nobody reloads U in
+    // mid-stream; otherwise every workgroup takes a contiguous, equal share of all items.
+    // (Workgroups that are neighbours in this order run on the same XCD, so a U[xi] slice shared by
+    // several of them is fetched into one L2 only.)
     const unsigned wg = xcd_local_block_id(blockIdx.x, gridDim.x);
-    const int g0 = (int)((long long)items_total * wg / gridDim.x);
-    const int g1 = (int)((long long)items_total * (wg + 1) / gridDim.x);
+    int g0, g1;
+    if (wgs_per_seg > 0) {
+        const int seg0 = wg / wgs_per_seg, part = wg - seg0 * wgs_per_seg;
+        g0 = seg0 * stages_per_xi + (int)((long long)stages_per_xi * part / wgs_per_seg);
+        g1 = seg0 * stages_per_xi + (int)((long long)stages_per_xi * (part + 1) / wgs_per_seg);
+    } else {
+        g0 = (int)((long long)items_total * wg / gridDim.x);
+        g1 = (int)((long long)items_total * (wg + 1) / gridDim.x);
+    }
     if (g0 >= g1) return;
-    const int per_kg = xi_count * stages_per_xi;
 
-    // Piece p = tid + 256*i of a stage sits at LDS offset 16*p: row r = p/4 of the stage
+    // Piece p = tid + THREADS*i of a stage sits at LDS offset 16*p: row r = p/4 of the stage
     // ([channel block][tile] order), physical 16-byte slot p%4.  The logical slot (which 8 channels
     // of the row) is XOR-ed with (r/4)%4, so that the 16 rows a 128-bit fragment read touches in one
     // phase fall into 16 different bank groups.  Each lane picks the global address that belongs in
     // its fixed LDS slot.
-    int p_row[NP];
-    size_t p_off[NP];
-#pragma unroll
-    for (int i = 0; i < NP; ++i) {
-        const int p = tid + i * 256;
-        const int r = p >> 2;
-        const int cb = r / SR;
-        const int q = (p & 3) ^ ((r >> 2) & 3);
-        p_row[i] = r % SR;
-        p_off[i] = (size_t)cb * T * kChanBlock + q * 8;
-    }
-    auto issue_stage = [&](int g, int slot) __attribute__((always_inline)) {
-        // past the end of the range the loads are still issued (the wait counts assume a fixed
-        // number per stage) but all lanes read the first 16 bytes of V: one cached request
-        const bool surplus = g > g1 - 1;
-        if (surplus) g = g1 - 1;
-        const int rem = g % per_kg;
-        const int xi = rem / stages_per_xi, tb = rem - xi * stages_per_xi;
-        const f16 *base = V + (size_t)xi * CB * T * kChanBlock;
-#pragma unroll
-        for (int i = 0; i < NP; ++i) {
-            int t = tb * SR + p_row[i]; if (t > T - 1) t = T - 1;      // rows past the end: reread the last
-            const f16 *src = surplus ? V : base + p_off[i] + (size_t)t * kChanBlock;
-            stream_to_lds16(src, ring_base + slot * STAGE_BYTES + (i * 256 + wave * 64) * 16);
-        }
-    };
+    const int p_q = (tid & 3) ^ ((tid >> 4) & 3);        // (r/4)%4 with r = tid/4 + (THREADS/4)*i
+    // fragment reads: row cb*SR + wm*32 + frag_row, logical slot 2*kk + lane/32
+    const int swz = (frag_row >> 2) & 3;                 // (r/4)%4 of those rows (SR is a multiple of 32)
+    int frag_off[2];
+    for (int kk = 0; kk < 2; ++kk) frag_off[kk] = (wm * 32 + frag_row) * 64 + (((kk * 2 + (lane >> 5)) ^ swz) * 16);
+    const unsigned u_lane_off = (unsigned)((frag_row * kChanBlock + (lane >> 5) * 8) * (int)sizeof(f16));
 
-    half8 ufrag[2][CB][2];                        // this wave's 64 output channels x all C channels of U[xi]
-    int held = -1;                                // item / stages_per_xi of the fragments held
-    auto load_u = [&](int kg, int xi) __attribute__((always_inline)) {
+    // One pass of the outer loop = the part of this workgroup's range that lies in one segment.
+    for (int g = g0; g < g1;) {
+        const int seg = g / stages_per_xi;                 // = kg * xi_count + xi
+        const int kg = seg / xi_count, xi = seg - kg * xi_count;
+        const int tb0 = g - seg * stages_per_xi;
+        int count = stages_per_xi - tb0;                   // stages of this pass
+        if (count > g1 - g) count = g1 - g;
+        g += count;
+        const f16 *v_plane = uniform_pointer(V + (size_t)xi * CB * T * kChanBlock);
+
+        // stage j of the pass -> ring slot; past the end of the pass the loads are still issued
+        // (the wait counts assume a fixed number per stage) but every lane rereads the first 16
+        // bytes of the plane: one cached request
+        auto issue_stage = [&](int j, int slot) __attribute__((always_inline)) {
+            const bool surplus = j > count - 1;
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            const int k = (kg * WN + wn) * 64 + nb * 32 + frag_row;       // < Kp: Kp is a multiple of WN*64
+            for (int i = 0; i < NP; ++i) {
+                const int r = (tid >> 2) + i * (THREADS / 4);    // row of the stage: [channel block][tile]
+                const int cb = r / SR, row = r % SR;             // SR is a power of two
+                int t = (tb0 + j) * SR + row; if (t > T - 1) t = T - 1;      // rows past the end: reread the last
+                const unsigned off = surplus ? 0u : (unsigned)(((cb * T + t) * kChanBlock + p_q * 8) * (int)sizeof(f16));
+                stream_to_lds16(v_plane, off, ring_base + slot * STAGE_BYTES + (i * THREADS + wave * 64) * 16);
+            }
+        };
+        for (int j = 0; j < S - 1; ++j) issue_stage(j, j);       // S-1 stages in flight
+
+        // this wave's NB*32 output channels x all C channels of U[xi], as ready-made MFMA fragments:
+        // uniform base per (block of 32 channels out, block of 32 channels in) + one per-lane offset
+        half8 ufrag[NB][CB][2];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int k0 = ((kg * WN + wn) * NB + nb) * 32;               // k0 + 31 < Kp: Kp is a multiple of WN*NB*32
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb) {
+                const f16 *blk = U + (((size_t)xi * CB + cb) * Kp + k0) * kChanBlock;
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk)
+                    ufrag[nb][cb][kk] = *reinterpret_cast<const NOVA_GLOBAL half8 *>(plane_element(blk + kk * 16, u_lane_off));
+            }
+        }
+        // Pin the fragments here: each empty statement below consumes and redefines one of them, so
+        // the compiler must have the load issued and waited for at this point and cannot sink either
+        // into the loop.  Its wait for the youngest of them is vmcnt(0), which also covers the S-1
+        // stages above (they are older); from here on only operations issued through inline
+        // assembly are outstanding, as the counts in the loop assume.
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-                for (int kk = 0; kk < 2; ++kk)
-                    ufrag[nb][cb][kk] = *reinterpret_cast<const half8 *>(
-                        U + (((size_t)xi * CB + cb) * Kp + k) * kChanBlock + kk * 16 + (lane >> 5) * 8);
-        }
-    };
+                for (int kk = 0; kk < 2; ++kk) asm volatile("" : "+v"(ufrag[nb][cb][kk]));
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    // prologue: S-1 stages in flight
-    for (int j = 0; j < S - 1; ++j) issue_stage(g0 + j, j);
-
-    int slot = 0;
-    for (int g = g0; g < g1; ++g) {
-        stream_wait_stage<0, S, NP, NS>(g - g0);           // this wave's pieces of stage g have landed
-        __syncthreads();                                   // everyone's have; slot-1 is free again
-        issue_stage(g + S - 1, slot == 0 ? S - 1 : slot - 1);
-
-        const int seg = g / stages_per_xi;                 // = kg * xi_count + xi
-        const int kg = seg / xi_count, xi = seg - kg * xi_count, tb = g - seg * stages_per_xi;
-        if (seg != held) {
-            load_u(kg, xi);
-            held = seg;
-            // wait inside the branch, or the compiler's waits for these loads land after the join
-            __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0)
-        }
-
-        // acc[nb] = U-block (32 output channels) x V-stage rows (32 tiles): D[row = k][col = t]
-        float16v acc[2];
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[nb][e] = 0.0f;
-        const unsigned char *stage = ring + slot * STAGE_BYTES;
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const int r = cb * SR + wm * 32 + frag_row;
-                const int phys = (kk * 2 + (lane >> 5)) ^ ((r >> 2) & 3);
-                const half8 vf = *reinterpret_cast<const half8 *>(stage + r * 64 + phys * 16);
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ufrag[0][cb][kk], vf, acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ufrag[1][cb][kk], vf, acc[1], 0, 0, 0);
-            }
-
+        MT *m_plane = uniform_pointer(Mo + ((size_t)xi * k_blocks + (size_t)(kg * WN + wn) * NB) * Tp * kChanBlock);
         // lane holds t = lane%32 and output channels 8*(e/4) + 4*(lane/32) + e%4 of each block:
         // four consecutive channels per store; rows up to Tp exist, so no store is conditional
-        const int t = tb * SR + wm * 32 + frag_row;
-        MT *dst = Mo + (((size_t)xi * k_blocks + (kg * WN + wn) * 2) * Tp + t) * kChanBlock + (lane >> 5) * 4;
+        unsigned m_off = (unsigned)(((tb0 * SR + wm * 32 + frag_row) * kChanBlock + (lane >> 5) * 4) * (int)sizeof(MT));
+        int slot = 0;
+        for (int j = 0; j < count; ++j) {
+            stream_wait_stage<0, S, NP, NS>(j);                // this wave's pieces of stage j have landed
+            __syncthreads();                                   // everyone's have; slot-1 is free again
+            issue_stage(j + S - 1, slot == 0 ? S - 1 : slot - 1);
+
+            // acc[nb] = U-block (32 output channels) x V-stage rows (32 tiles): D[row = k][col = t]
+            float16v acc[NB];
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+            for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                stream_store(dst + (size_t)nb * Tp * kChanBlock + q * 8, acc[nb][4 * q], acc[nb][4 * q + 1],
-                             acc[nb][4 * q + 2], acc[nb][4 * q + 3]);
-        slot = slot == S - 1 ? 0 : slot + 1;
+                for (int e = 0; e < 16; ++e) acc[nb][e] = 0.0f;
+            const unsigned char *stage = ring + slot * STAGE_BYTES;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk) {
+                    const half8 vf = *reinterpret_cast<const half8 *>(stage + cb * SR * 64 + frag_off[kk]);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ufrag[nb][cb][kk], vf, acc[nb], 0, 0, 0);
+                    // keep the fragment reads of later channel blocks from being hoisted all the way
+                    // up: sixteen 128-bit fragments in flight at once do not fit the register budget
+                    if (kk == 1) __builtin_amdgcn_sched_barrier(0);
+                }
+
+            // The stores are inline assembly and read the accumulators directly; the compiler inserts
+            // the wait states an MFMA result needs before a vector-memory instruction may read it
+            // only for instructions it schedules itself, so they are spelled out here (the longest
+            // requirement, for a 16-pass MFMA, is 18).
+            asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                MT *plane = m_plane + (size_t)nb * Tp * kChanBlock;
+                stream_store<0 * 8 * (int)sizeof(MT)>(plane, m_off, acc[nb][0], acc[nb][1], acc[nb][2], acc[nb][3]);
+                stream_store<1 * 8 * (int)sizeof(MT)>(plane, m_off, acc[nb][4], acc[nb][5], acc[nb][6], acc[nb][7]);
+                stream_store<2 * 8 * (int)sizeof(MT)>(plane, m_off, acc[nb][8], acc[nb][9], acc[nb][10], acc[nb][11]);
+                stream_store<3 * 8 * (int)sizeof(MT)>(plane, m_off, acc[nb][12], acc[nb][13], acc[nb][14], acc[nb][15]);
+            }
+            m_off += SR * kChanBlock * (int)sizeof(MT);
+            slot = slot == S - 1 ? 0 : slot + 1;
+        }
+        // the surplus prefetches of the tail must land before the ring is refilled or released,
+        // and every wave must be done reading before the next pass overwrites it
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // surplus tail prefetches must land before the LDS is released
 }
 
 // binary32: 64 x 64 tile, 256 threads, 4 x 4 outputs per thread
@@ -399,19 +444,25 @@ static int launch_c16(const void *U, const void *V, void *Mo, const Geometry &g,
     return (int)hipGetLastError();
 }
 
-template <int WN, int CB, int S, typename MT>
+template <int WN, int WM, int NB, int CB, int S, int OCC, typename MT>
 static int launch_stream(const void *U, const void *V, void *Mo, const Geometry &g, hipStream_t stream)
 {
-    constexpr int SR = 32 * (4 / WN);
-    const int cu_count = device_cu_count();
+    constexpr int SR = 32 * WM;
+    const int slots = device_cu_count() * OCC;           // workgroups resident at once
     const int stages_per_xi = ceil_div((int)g.T, SR);
-    const int kgroups = g.Kp / (WN * 64);
-    const long long items = (long long)kgroups * g.n * g.n * stages_per_xi;
+    const int kgroups = g.Kp / (WN * NB * 32);
+    const long long segs = (long long)kgroups * g.n * g.n;
+    const long long items = segs * stages_per_xi;
     if (items <= 0 || items > 0x7fffffffLL) return (int)hipErrorInvalidValue;
-    const int blocks = (int)(items < cu_count ? items : cu_count);
-    hipLaunchKernelGGL((contract_stream_kernel<WN, CB, S, MT>), dim3(blocks), dim3(256), 0, stream,
+    // 32-bit byte offsets inside one xi plane of V and one (xi, channel block) plane of M
+    if ((size_t)g.c_blocks * g.T * kChanBlock * sizeof(f16) >= ((size_t)1 << 32) ||
+        (size_t)g.Tp * kChanBlock * sizeof(MT) >= ((size_t)1 << 32)) return (int)hipErrorInvalidValue;
+    int wgs_per_seg = (int)(slots / segs);
+    if (wgs_per_seg > stages_per_xi) wgs_per_seg = stages_per_xi;
+    const int blocks = wgs_per_seg > 0 ? (int)(segs * wgs_per_seg) : (int)(items < slots ? items : slots);
+    hipLaunchKernelGGL((contract_stream_kernel<WN, WM, NB, CB, S, OCC, MT>), dim3(blocks), dim3(64 * WN * WM), 0, stream,
                        (const f16 *)U, (const f16 *)V, (MT *)Mo, (int)g.T, (int)g.Tp, g.Kp, g.k_blocks,
-                       stages_per_xi, g.n * g.n, (int)items);
+                       stages_per_xi, g.n * g.n, (int)items, wgs_per_seg);
     return (int)hipGetLastError();
 }
 
@@ -431,14 +482,15 @@ static int launch_c16_shape(const void *U, const void *V, void *Mo, const Geomet
     const int cb = g.c_blocks;
     const int wn = g.Kp % 256 == 0 ? 4 : g.Kp % 128 == 0 ? 2 : g.Kp % 64 == 0 ? 1 : 0;
     if (kUseStreamKernel) {
-        if (wn == 4 && cb == 8) return launch_stream<4, 8, 8, MT>(U, V, Mo, g, s);   // 16 KiB stages
-        if (wn == 4 && cb == 4) return launch_stream<4, 4, 8, MT>(U, V, Mo, g, s);   //  8 KiB
-        if (wn == 4 && cb == 2) return launch_stream<4, 2, 8, MT>(U, V, Mo, g, s);   //  4 KiB
-        if (wn == 2 && cb == 8) return launch_stream<2, 8, 4, MT>(U, V, Mo, g, s);   // 32 KiB
-        if (wn == 2 && cb == 4) return launch_stream<2, 4, 8, MT>(U, V, Mo, g, s);   // 16 KiB
-        if (wn == 2 && cb == 2) return launch_stream<2, 2, 8, MT>(U, V, Mo, g, s);   //  8 KiB
-        if (wn == 1 && cb == 4) return launch_stream<1, 4, 4, MT>(U, V, Mo, g, s);   // 32 KiB
-        if (wn == 1 && cb == 2) return launch_stream<1, 2, 8, MT>(U, V, Mo, g, s);   // 16 KiB
+        //                                            WN WM NB CB  S OCC
+        if (wn == 4 && cb == 8) return launch_stream<8, 1, 1, 8, 4, 2, MT>(U, V, Mo, g, s);   // 8 waves x 32 channels
+        if (wn == 4 && cb == 4) return launch_stream<4, 1, 2, 4, 8, 2, MT>(U, V, Mo, g, s);
+        if (wn == 4 && cb == 2) return launch_stream<4, 1, 2, 2, 8, 2, MT>(U, V, Mo, g, s);
+        if (wn == 2 && cb == 8) return launch_stream<2, 2, 2, 8, 4, 1, MT>(U, V, Mo, g, s);
+        if (wn == 2 && cb == 4) return launch_stream<2, 2, 2, 4, 4, 2, MT>(U, V, Mo, g, s);
+        if (wn == 2 && cb == 2) return launch_stream<2, 2, 2, 2, 8, 2, MT>(U, V, Mo, g, s);
+        if (wn == 1 && cb == 4) return launch_stream<1, 4, 2, 4, 4, 1, MT>(U, V, Mo, g, s);
+        if (wn == 1 && cb == 2) return launch_stream<1, 4, 2, 2, 4, 2, MT>(U, V, Mo, g, s);
     }
     return launch_c16_tiled<MT>(U, V, Mo, g, s);       // other shapes: tiled kernel
 }

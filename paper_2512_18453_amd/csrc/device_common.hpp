@@ -65,6 +65,18 @@ __device__ __forceinline__ NOVA_GLOBAL P *plane_element(P *uniform_base, unsigne
     return reinterpret_cast<NOVA_GLOBAL P *>(base + byte_offset);
 }
 
+// The same pointer, read from the first active lane into scalar registers: for values every lane
+// computes alike but which the compiler keeps in vector registers (inline-assembly operands with
+// an "s" constraint need them in scalar ones).
+template <typename P>
+__device__ __forceinline__ P *uniform_pointer(P *p)
+{
+    const unsigned long long bits = reinterpret_cast<unsigned long long>(p);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)bits);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(bits >> 32));
+    return reinterpret_cast<P *>(((unsigned long long)hi << 32) | lo);
+}
+
 // blockIdx.x -> logical block id such that consecutive logical ids run on the same XCD
 // (hardware deals consecutive workgroup ids round-robin over the 8 XCDs, each with its own L2).
 __device__ __forceinline__ unsigned xcd_local_block_id(unsigned id, unsigned total)
