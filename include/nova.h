@@ -120,8 +120,8 @@ int nova_filter_transform(const nova_transforms *t, const void *w, int K, int C,
 /*
  * Workspace for nova_winograd_conv2d.  The call processes the batch in slabs of whole images so
  * that V and M of a slab stay cache resident; the slab size follows from the workspace it is
- * given.  images_per_slab = 0 asks for the library's default (as many images as fit 2 GiB of
- * V and M, which is the whole batch for common layers), N for the whole batch in one pass.  Returns 0 for invalid arguments.
+ * given.  images_per_slab = 0 asks for the library's default (as many images as fit 256 MiB of
+ * V and M, at least one), N for the whole batch in one pass.  Returns 0 for invalid arguments.
  */
 size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K, int m, int dtype, int flags,
                                    int images_per_slab);

@@ -44,7 +44,10 @@ static size_t m_bytes(const Geometry &g, int dtype, int flags)
     return (size_t)g.n * g.n * g.k_blocks * (size_t)g.Tp * kChanBlock * es;
 }
 
-constexpr size_t kDefaultSlabBytes = (size_t)2 << 30;
+// V and M of a slab together: the size of the last-level cache (256 MB), so that what one stage
+// writes is still there when the next reads it.  Measured on 224 x 224 and 112 x 112 VGG layers
+// (batch 32): 7-10 % faster than the whole batch in one pass, and faster than smaller slabs.
+constexpr size_t kDefaultSlabBytes = (size_t)256 << 20;
 
 }  // namespace nova
 

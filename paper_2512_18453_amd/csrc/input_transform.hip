@@ -2,7 +2,8 @@
 // zero-padded image, x [N][C][H][W] -> V [n*n][C/32][T][32].
 //
 // One workgroup takes one image, one tile row, a group of TWB neighbouring tiles and one block
-// of 32 channels.  The 32-channel x (n rows) x (TWB*m + 2 columns) input strip is staged in LDS
+// of 32 channels (for narrow images, where a tile row has few tiles: TRB neighbouring tile rows
+// of full width).  The 32-channel x (TRB*m + 2 rows) x (TWB*m + 2 columns) input strip is staged in LDS
 // in the order it has in memory (16-byte pieces when W allows, all loads of a round in flight
 // together), with a channel pitch that puts the 32 channels of a half-wave into 32 different
 // banks for the per-thread tile reads (thread = one tile x one channel, 32 consecutive lanes =
@@ -73,13 +74,25 @@ template <int N> struct RowSplit { static constexpr int value = ((N / 2) % 2 == 
 // 4 * odd elements: rows stay 8-byte aligned for the staging writes, and the 32 channels that a
 // half-wave reads at one (row, column) fall into 32 different banks.
 struct StripShape {
-    int twb;         // tiles per group
+    int twb;         // tiles per group (all tile rows of the group together)
+    int trb;         // tile rows per group; > 1 only if a group spans the image width
+    int rows;        // strip rows = trb * m + 2
+    unsigned rows_magic;    // ceil(2^32 / rows)
     int groups;      // tile groups per tile row
     int pieces;      // 16-byte pieces per strip row (vector path) / columns per row (scalar path)
     int row_pitch;   // elements
     int ch_pitch;    // elements
     unsigned piece_magic;   // ceil(2^32 / pieces): s / pieces == mulhi(s, magic) while s * pieces < 2^32
+    unsigned w_magic;       // the same for W (flat staging)
 };
+
+// How the strip gets into LDS.
+//   kStageScalar  any W, any group: element by element, lanes along W
+//   kStageVec     W a multiple of a 16-byte piece and x 16-byte aligned: pieces never straddle rows
+//   kStageFlat    the group spans the whole image width (narrow images) and x is 16-byte aligned:
+//                 the rows a strip needs are one contiguous run of each channel plane, fetched in
+//                 aligned 16-byte pieces whatever W is and scattered to their (row, column) in LDS
+enum { kStageScalar = 0, kStageVec = 1, kStageFlat = 2 };
 
 template <int N, typename T, bool SYM, bool ALIGNED, int LO, int HI>
 __device__ __forceinline__ void transform_rows_of_tile(const T *tile, int row_pitch, T *mine, int xi_pitch,
@@ -131,12 +144,13 @@ __device__ __forceinline__ void transform_rows_of_tile(const T *tile, int row_pi
     }
 }
 
-template <int N, typename T, bool SYM, bool VEC>
+template <int N, typename T, bool SYM, int STG>
 __global__ void __launch_bounds__(512)
 input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H, int W,
-                       int tiles_h, int tiles_w, int c_blocks, long long Ttot, StripShape sh,
-                       InCoef<N> coef)
+                       int tiles_h, int tiles_w, int c_blocks, long long Ttot, long long x_elems,
+                       StripShape sh, InCoef<N> coef)
 {
+    constexpr bool VEC = STG == kStageVec;
     constexpr int M = N - 2;
     constexpr int PE = 16 / (int)sizeof(T);      // elements per 16-byte piece
     constexpr int SP = RowSplit<N>::value;
@@ -147,12 +161,13 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
 
     // block -> (image, channel block, tile row, tile group); group fastest
     unsigned bid = xcd_local_block_id(blockIdx.x, gridDim.x);
+    const int row_groups = (tiles_h + sh.trb - 1) / sh.trb;
     const int tg = bid % sh.groups; bid /= sh.groups;
-    const int tr = bid % tiles_h; bid /= tiles_h;
+    const int tr = (bid % row_groups) * sh.trb; bid /= row_groups;      // first tile row of the group
     const int cb = bid % c_blocks; bid /= c_blocks;
     const int img = bid;
 
-    const int tc0 = tg * sh.twb;
+    const int tc0 = sh.trb > 1 ? 0 : tg * sh.twb;
     const int h_lo = tr * M - 1;          // image row of strip row 0
     const int w_lo = tc0 * M - 1;         // first image column the group needs
     int w_al = w_lo;                      // image column of strip column 0
@@ -162,7 +177,7 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
         // W is a multiple of PE and x is 16-byte aligned: every piece is wholly inside or outside
         // the image.  All loads of a round are issued before the first LDS write waits on them.
         w_al = (w_lo + PE) / PE * PE - PE;        // floor to a multiple of PE (w_lo >= -1)
-        const int slots = kChanBlock * N * sh.pieces;
+        const int slots = kChanBlock * sh.rows * sh.pieces;
         constexpr int R = 8;                      // usually the whole strip in one round trip
         for (int base = threadIdx.x; base < slots; base += R * (int)blockDim.x) {
             u32x4 val[R];
@@ -172,7 +187,7 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
                 const int s = base + r * (int)blockDim.x;
                 const int line = (int)__umulhi((unsigned)s, sh.piece_magic);
                 const int q = s - line * sh.pieces;
-                const int c_in = line / N, a = line - c_in * N;
+                const int c_in = (int)__umulhi((unsigned)line, sh.rows_magic), a = line - c_in * sh.rows;
                 const int c = cb * kChanBlock + c_in, h = h_lo + a, w = w_al + q * PE;
                 const bool ok = s < slots && c < C && h >= 0 && h < H && w >= 0 && w < W;
                 dst[r] = s < slots ? c_in * sh.ch_pitch + a * sh.row_pitch + q * PE : -1;
@@ -187,10 +202,73 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
                     p[1] = u32x2{val[r].z, val[r].w};
                 }
         }
+    } else if constexpr (STG == kStageFlat) {
+        // The group spans the image width (tc0 = 0, w_lo = -1).  Rows h0..h1 of one channel are one
+        // run of (h1 - h0 + 1) * W elements; it is covered with 16-byte pieces aligned in x (their
+        // ends may belong to neighbouring rows or channels: those elements are dropped), and every
+        // element goes to its own (row, column) of the strip.  What the image does not cover
+        // (halo column and rows, tile padding) is zeroed first.
+        {
+            const int words = kChanBlock * sh.ch_pitch * (int)sizeof(T) / 8;     // ch_pitch: a multiple of 4 elements
+            u32x2 *z = reinterpret_cast<u32x2 *>(lds);
+            for (int s = threadIdx.x; s < words; s += (int)blockDim.x) z[s] = u32x2{0u, 0u};
+        }
+        __syncthreads();
+        const int h0 = h_lo < 0 ? 0 : h_lo;
+        const int h1 = h_lo + sh.rows - 1 > H - 1 ? H - 1 : h_lo + sh.rows - 1;
+        const int run = (h1 - h0 + 1) * W;
+        const int slots = kChanBlock * sh.pieces;
+        constexpr int R = 4;
+        for (int base = threadIdx.x; base < slots; base += R * (int)blockDim.x) {
+            T val[R][PE];
+            int rel[R], c_of[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int s = base + r * (int)blockDim.x;
+                const int c_in = (int)__umulhi((unsigned)s, sh.piece_magic);
+                const int k = s - c_in * sh.pieces;
+                const int c = cb * kChanBlock + c_in;
+                const long long e0 = (((long long)img * C + c) * H + h0) * W;     // first element of the run
+                const long long p0 = (e0 & ~(long long)(PE - 1)) + (long long)k * PE;
+                rel[r] = (int)(p0 - e0);                                           // -(PE-1) .. run-1 if needed
+                c_of[r] = c_in;
+                const bool ok = s < slots && c < C && rel[r] < run;
+                if (!ok) rel[r] = run;                                             // nothing of it is used
+#pragma unroll
+                for (int e = 0; e < PE; ++e) val[r][e] = (T)0.0f;
+                if (ok) {
+                    if (p0 + PE <= x_elems) {
+                        const u32x4 piece = *reinterpret_cast<const u32x4 *>(x + p0);
+                        __builtin_memcpy(val[r], &piece, 16);
+                    } else {
+                        // the last piece of x when its size is not a multiple of a piece
+#pragma unroll
+                        for (int e = 0; e < PE; ++e)
+                            if (p0 + e < x_elems) val[r][e] = x[p0 + e];
+                    }
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                // (row, column) of the first element that belongs to the run, then step along it
+                int q = rel[r] < 0 ? 0 : rel[r];
+                int hr = (int)__umulhi((unsigned)q, sh.w_magic);
+                int w = q - hr * W;
+                T *row0 = lds + c_of[r] * sh.ch_pitch + (h0 - h_lo) * sh.row_pitch + 1;    // column of w = 0
+#pragma unroll
+                for (int e = 0; e < PE; ++e) {
+                    const int pos = rel[r] + e;
+                    if (pos >= 0 && pos < run) {
+                        row0[hr * sh.row_pitch + w] = val[r][e];
+                        if (++w == W) { w = 0; ++hr; }
+                    }
+                }
+            }
+        }
     } else {
         // any W: element-wise, lanes along W
         const int cols = sh.pieces;
-        const int slots = kChanBlock * N * cols;
+        const int slots = kChanBlock * sh.rows * cols;
         constexpr int R = 8;
         for (int base = threadIdx.x; base < slots; base += R * (int)blockDim.x) {
             T val[R];
@@ -200,7 +278,7 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
                 const int s = base + r * (int)blockDim.x;
                 const int line = (int)__umulhi((unsigned)s, sh.piece_magic);
                 const int q = s - line * cols;
-                const int c_in = line / N, a = line - c_in * N;
+                const int c_in = (int)__umulhi((unsigned)line, sh.rows_magic), a = line - c_in * sh.rows;
                 const int c = cb * kChanBlock + c_in, h = h_lo + a, w = w_al + q;
                 const bool ok = s < slots && c < C && h >= 0 && h < H && w >= 0 && w < W;
                 dst[r] = s < slots ? c_in * sh.ch_pitch + a * sh.row_pitch + q : -1;
@@ -220,8 +298,10 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
     // independent once no +a/-a pair is cut).  The results are collected in registers first ...
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int j = (wave >> 1) * 2 + (lane >> 5), c_in = lane & 31, half = wave & 1;
-    const bool active = j < sh.twb && tc0 + j < tiles_w;
-    const T *tile = lds + c_in * sh.ch_pitch + (w_lo - w_al) + j * M;
+    int jr = 0, jc = j;                       // tile row and column inside the group
+    if (sh.trb > 1) { jr = j / tiles_w; jc = j - jr * tiles_w; }
+    const bool active = j < sh.twb && tc0 + jc < tiles_w && tr + jr < tiles_h;
+    const T *tile = lds + c_in * sh.ch_pitch + jr * M * sh.row_pitch + (w_lo - w_al) + jc * M;
     constexpr int ROWS_MAX = SP > N - SP ? SP : N - SP;
     T res[ROWS_MAX * N];
     if (active) {
@@ -244,7 +324,12 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
     __syncthreads();
     {
         constexpr int PPR = kChanBlock / PE;               // 16-byte pieces per (xi, tile) row
+        // tiles of the group that exist; consecutive tile rows of full width are adjacent in t
         int valid = tiles_w - tc0; if (valid > sh.twb) valid = sh.twb; if (valid < 0) valid = 0;
+        if (sh.trb > 1) {
+            int tile_rows = tiles_h - tr; if (tile_rows > sh.trb) tile_rows = sh.trb;
+            valid = tile_rows * tiles_w;
+        }
         const long long t0 = ((long long)img * tiles_h + tr) * tiles_w + tc0;
         const size_t in_plane = ((size_t)cb * Ttot + t0) * kChanBlock;
         const size_t xi_stride = (size_t)c_blocks * Ttot * kChanBlock;
@@ -274,13 +359,17 @@ static void fill_in_coef(const nova_transforms *t, InCoef<N> &k)
         }
 }
 
-// Strip geometry for `twb` tiles per group; returns the LDS bytes it needs.
+// Strip geometry for groups of `trb` tile rows x `twb` tiles; returns the LDS bytes it needs.
 template <int N, typename T>
-static size_t strip_shape(int twb, bool vec, StripShape &sh)
+static size_t strip_shape(int twb, int trb, bool vec, StripShape &sh)
 {
+    sh.w_magic = 0;
     constexpr int M = N - 2;
     constexpr int PE = 16 / (int)sizeof(T);
     const int need = twb * M + 2;                       // columns w_lo .. w_lo + need - 1
+    sh.trb = trb;
+    sh.rows = trb * M + 2;
+    sh.rows_magic = (unsigned)((((unsigned long long)1 << 32) + sh.rows - 1) / sh.rows);
     if (vec) {
         // worst-case offset of w_lo inside its piece is PE - 1
         sh.pieces = (need + PE - 1 + PE - 1) / PE;
@@ -292,10 +381,10 @@ static size_t strip_shape(int twb, bool vec, StripShape &sh)
     // channel pitch: an odd multiple of 16 bytes on the vector path (aligned 128-bit reads, and the
     // 16 lanes of one read phase cover all 64 banks), else 4 * odd elements
     const int unit = vec ? 16 / (int)sizeof(T) : 4;
-    int chp = (N * sh.row_pitch + unit - 1) / unit * unit;
+    int chp = (sh.rows * sh.row_pitch + unit - 1) / unit * unit;
     if ((chp / unit) % 2 == 0) chp += unit;
     sh.ch_pitch = chp;
-    sh.twb = twb;
+    sh.twb = twb * trb;
     sh.piece_magic = (unsigned)((((unsigned long long)1 << 32) + sh.pieces - 1) / sh.pieces);
     return (size_t)kChanBlock * chp * sizeof(T);
 }
@@ -310,25 +399,45 @@ static int launch_it(const nova_transforms *t, const void *x, void *V, const Geo
     // tiles per group: at most 8 (two waves per tile pair, 512 threads); the LDS block holds first
     // the strip, then the results [xi][tile][32], and may take at most 64 KiB
     StripShape sh;
-    auto lds_need = [&](int twb) {
-        const size_t strip = strip_shape<N, T>(twb, vec, sh);
-        const size_t out_stage = (size_t)N * N * twb * kChanBlock * sizeof(T);
+    auto lds_need = [&](int twb, int trb) {
+        const size_t strip = strip_shape<N, T>(twb, trb, vec, sh);
+        const size_t out_stage = (size_t)N * N * twb * trb * kChanBlock * sizeof(T);
         return strip > out_stage ? strip : out_stage;
     };
     int twb_max = 8;
-    while (twb_max > 1 && lds_need(twb_max) > 64 * 1024) --twb_max;
+    while (twb_max > 1 && lds_need(twb_max, 1) > 64 * 1024) --twb_max;
     sh.groups = ceil_div(g.tiles_w, twb_max);
-    const int twb = ceil_div(g.tiles_w, sh.groups);
-    const size_t lds_bytes = lds_need(twb);
+    const int twb = ceil_div(g.tiles_w, sh.groups);      // tiles of one tile row per group
+    // narrow images: a group spans the width; give it as many tile rows as keep it within 8 tiles
+    int trb = 1;
+    if (sh.groups == 1) {
+        trb = 8 / twb;
+        if (trb > g.tiles_h) trb = g.tiles_h;
+        while (trb > 1 && lds_need(twb, trb) > 64 * 1024) --trb;
+    }
+    trb = ceil_div(g.tiles_h, ceil_div(g.tiles_h, trb));    // same number of groups, evenly sized
+    const size_t lds_bytes = lds_need(twb, trb);         // (leaves sh.groups alone)
     if (lds_bytes > 64 * 1024 || sh.pieces < 2) return (int)hipErrorInvalidValue;
-    const int threads = ((twb + 1) / 2) * 128;           // a pair of waves per pair of tiles
-    const long long blocks = (long long)sh.groups * g.tiles_h * g.c_blocks * g.N;
+    // narrow images whose width is not a whole number of pieces: flat staging
+    const bool flat = !vec && sh.groups == 1 && ((uintptr_t)x % 16) == 0 && (long long)sh.rows * g.W < (1 << 15);
+    if (flat) {
+        sh.pieces = (sh.rows * g.W + 2 * (PE - 1)) / PE;    // pieces that can touch a run of rows*W elements
+        sh.piece_magic = (unsigned)((((unsigned long long)1 << 32) + sh.pieces - 1) / sh.pieces);
+        sh.w_magic = (unsigned)((((unsigned long long)1 << 32) + g.W - 1) / g.W);
+    }
+    const int threads = ((sh.twb + 1) / 2) * 128;        // a pair of waves per pair of tiles
+    const long long blocks = (long long)sh.groups * ceil_div(g.tiles_h, trb) * g.c_blocks * g.N;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
-    void (*kern)(const T *, T *, int, int, int, int, int, int, long long, StripShape, InCoef<N>);
-    if (t->symmetric) kern = vec ? input_transform_kernel<N, T, true, true> : input_transform_kernel<N, T, true, false>;
-    else              kern = vec ? input_transform_kernel<N, T, false, true> : input_transform_kernel<N, T, false, false>;
+    void (*kern)(const T *, T *, int, int, int, int, int, int, long long, long long, StripShape, InCoef<N>);
+    if (t->symmetric)
+        kern = vec ? input_transform_kernel<N, T, true, kStageVec>
+             : flat ? input_transform_kernel<N, T, true, kStageFlat> : input_transform_kernel<N, T, true, kStageScalar>;
+    else
+        kern = vec ? input_transform_kernel<N, T, false, kStageVec>
+             : flat ? input_transform_kernel<N, T, false, kStageFlat> : input_transform_kernel<N, T, false, kStageScalar>;
+    const long long x_elems = (long long)g.N * g.C * g.H * g.W;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds_bytes, stream,
-                       (const T *)x, (T *)V, g.C, g.H, g.W, g.tiles_h, g.tiles_w, g.c_blocks, g.T, sh, coef);
+                       (const T *)x, (T *)V, g.C, g.H, g.W, g.tiles_h, g.tiles_w, g.c_blocks, g.T, x_elems, sh, coef);
     return (int)hipGetLastError();
 }
 

@@ -2,13 +2,16 @@
 // y [N][K][H][W];  M [n*n][K/32][Tp][32] holds the channel-summed products (Tp = T rounded up to
 // a multiple of 128; the extra rows are never read).
 //
-// One workgroup takes one image, one tile row, a group of TWB neighbouring tiles and one block of
+// One workgroup takes one image, one tile row, a group of TWB neighbouring tiles (for narrow
+// images, where a tile row has few tiles: TRB neighbouring tile rows of full width) and one block of
 // 32 output channels; thread = one tile x one channel, so the n*n loads of a half-wave are 128
 // (fp32 M) contiguous bytes each and a workgroup reads TWB*128 contiguous bytes per xi.  The
 // m x m results go through LDS so that the global stores run along W.
 // For points given as 0, +a, -a, ... the rows of +a and -a enter only through their sum (even
 // output index) or difference (odd output index), which halves the multiplications.  Binary32
 // arithmetic, one rounding to the storage format at the store; optional fused ReLU.
+#include <type_traits>
+
 #include "device_common.hpp"
 
 namespace nova {
@@ -49,13 +52,25 @@ __device__ __forceinline__ void output_transform_1d(const float (&v)[N], float (
 }
 
 struct OutShape {
-    int twb;          // tiles per group
+    int twb;          // tiles per group (all tile rows of the group together)
+    int trb;          // tile rows per group; > 1 only if a group spans the image width
+    int rows;         // output rows per group = trb * m
     int groups;       // tile groups per tile row
     int cols_pitch;   // LDS elements per output row of the group
     int k_pitch;      // LDS elements per channel
+    int pieces;       // flat stores: 16-byte pieces that can touch one channel's run of rows * W elements
+    unsigned piece_magic, w_magic, rows_magic;     // ceil(2^32 / d) for d = pieces, W, rows
 };
 
-template <int N, typename T, typename MT, bool SYM, bool VEC, bool RELU>
+// How the block leaves LDS.
+//   kStoreScalar  any W, any group: element by element, lanes along W
+//   kStoreVec     W (and the group width) a multiple of a 16-byte piece, y 16-byte aligned
+//   kStoreFlat    the group spans the image width (narrow images) and y is 16-byte aligned: the rows
+//                 of one channel are one contiguous run of y, written in aligned 16-byte pieces
+//                 whatever W is (element stores at its two ragged ends)
+enum { kStoreScalar = 0, kStoreVec = 1, kStoreFlat = 2 };
+
+template <int N, typename T, typename MT, bool SYM, int STG, bool RELU>
 __global__ void __launch_bounds__(512)
 output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int H, int W,
                         int tiles_h, int tiles_w, int k_blocks, long long Ttot, OutShape sh,
@@ -69,15 +84,18 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
     T *lds = reinterpret_cast<T *>(lds_raw);
 
     unsigned bid = xcd_local_block_id(blockIdx.x, gridDim.x);
+    const int row_groups = (tiles_h + sh.trb - 1) / sh.trb;
     const int tg = bid % sh.groups; bid /= sh.groups;
-    const int tr = bid % tiles_h; bid /= tiles_h;
+    const int tr = (bid % row_groups) * sh.trb; bid /= row_groups;      // first tile row of the group
     const int kb = bid % k_blocks; bid /= k_blocks;
     const int img = bid;
-    const int tc0 = tg * sh.twb;
+    const int tc0 = sh.trb > 1 ? 0 : tg * sh.twb;
 
     const int j = threadIdx.x >> 5, k_in = threadIdx.x & 31;
-    if (j < sh.twb && tc0 + j < tiles_w) {
-        const long long t = ((long long)img * tiles_h + tr) * tiles_w + tc0 + j;
+    int jr = 0, jc = j;                       // tile row and column inside the group
+    if (sh.trb > 1) { jr = j / tiles_w; jc = j - jr * tiles_w; }
+    if (j < sh.twb && tc0 + jc < tiles_w && tr + jr < tiles_h) {
+        const long long t = ((long long)img * tiles_h + tr + jr) * tiles_w + tc0 + jc;
         // plane base of each xi is uniform (scalar registers); the offset inside the plane is per
         // thread and fits 32 bits (checked by the launcher)
         const size_t xi_stride = (size_t)k_blocks * Ttot * kChanBlock;
@@ -93,7 +111,7 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
 #pragma unroll
             for (int p = 0; p < M; ++p) z[p][b] = o[p];
         }
-        T *dst = lds + k_in * sh.k_pitch + j * M;
+        T *dst = lds + k_in * sh.k_pitch + jr * M * sh.cols_pitch + jc * M;
 #pragma unroll
         for (int p = 0; p < M; ++p) {
             float o[M];
@@ -108,19 +126,19 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
     }
     __syncthreads();
 
-    // ---- store the [32 channels][m rows][columns] block, lanes along W
+    // ---- store the [32 channels][rows][columns] block, lanes along W
     const int w0 = tc0 * M;
-    int cols = sh.twb * M;
+    int cols = (sh.trb > 1 ? tiles_w : sh.twb) * M;
     if (w0 + cols > W) cols = W - w0;
-    if constexpr (VEC) {
+    if constexpr (STG == kStoreVec) {
         // W, w0 and cols are multiples of PE and y is 16-byte aligned
         const int pieces = cols / PE;
         const unsigned magic = (unsigned)((((unsigned long long)1 << 32) + pieces - 1) / pieces);
-        const int slots = kChanBlock * M * pieces;
+        const int slots = kChanBlock * sh.rows * pieces;
         for (int s = threadIdx.x; s < slots; s += (int)blockDim.x) {
             const int line = pieces > 1 ? (int)__umulhi((unsigned)s, magic) : s;
             const int q = s - line * pieces;
-            const int kk = line / M, p = line - kk * M;
+            const int kk = (int)__umulhi((unsigned)line, sh.rows_magic), p = line - kk * sh.rows;
             const int k = kb * kChanBlock + kk, h = tr * M + p;
             if (k >= K || h >= H) continue;
             const u32x2 *in = reinterpret_cast<const u32x2 *>(lds + kk * sh.k_pitch + p * sh.cols_pitch + q * PE);
@@ -128,13 +146,53 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
             *reinterpret_cast<u32x4 *>(y + (((size_t)img * K + k) * H + h) * W + w0 + q * PE) =
                 u32x4{lo.x, lo.y, hi.x, hi.y};
         }
+    } else if constexpr (STG == kStoreFlat) {
+        // the group spans the width: rows h0 .. h1-1 of one channel are one run of y
+        const int h0 = tr * M;
+        int h1 = h0 + sh.rows; if (h1 > H) h1 = H;
+        const int run = (h1 - h0) * W;
+        const int slots = kChanBlock * sh.pieces;
+        for (int s = threadIdx.x; s < slots; s += (int)blockDim.x) {
+            const int kk = (int)__umulhi((unsigned)s, sh.piece_magic);
+            const int kq = s - kk * sh.pieces;
+            const int k = kb * kChanBlock + kk;
+            if (k >= K) continue;
+            const long long e0 = (((long long)img * K + k) * H + h0) * W;         // first element of the run
+            const long long p0 = (e0 & ~(long long)(PE - 1)) + (long long)kq * PE;   // piece, aligned in y
+            const int rel = (int)(p0 - e0);                                        // -(PE-1) .. run-1 if needed
+            if (rel >= run) continue;
+            // (row, column) of the piece's first element inside the run, then step along it
+            const int q = rel < 0 ? 0 : rel;
+            int hr = (int)__umulhi((unsigned)q, sh.w_magic);
+            int w = q - hr * W;
+            const T *src = lds + kk * sh.k_pitch;
+            T val[PE];
+#pragma unroll
+            for (int e = 0; e < PE; ++e) {
+                const int pos = rel + e;
+                val[e] = (T)0.0f;
+                if (pos >= 0 && pos < run) {
+                    val[e] = src[hr * sh.cols_pitch + w];
+                    if (++w == W) { w = 0; ++hr; }
+                }
+            }
+            if (rel >= 0 && rel + PE <= run) {
+                u32x4 piece;
+                __builtin_memcpy(&piece, val, 16);
+                *reinterpret_cast<u32x4 *>(y + p0) = piece;
+            } else {
+#pragma unroll
+                for (int e = 0; e < PE; ++e)
+                    if (rel + e >= 0 && rel + e < run) y[p0 + e] = val[e];
+            }
+        }
     } else {
         const unsigned magic = (unsigned)((((unsigned long long)1 << 32) + cols - 1) / cols);
-        const int slots = kChanBlock * M * cols;
+        const int slots = kChanBlock * sh.rows * cols;
         for (int s = threadIdx.x; s < slots; s += (int)blockDim.x) {
             const int line = cols > 1 ? (int)__umulhi((unsigned)s, magic) : s;
             const int q = s - line * cols;
-            const int kk = line / M, p = line - kk * M;
+            const int kk = (int)__umulhi((unsigned)line, sh.rows_magic), p = line - kk * sh.rows;
             const int k = kb * kChanBlock + kk, h = tr * M + p;
             if (k >= K || h >= H) continue;
             y[(((size_t)img * K + k) * H + h) * W + w0 + q] = lds[kk * sh.k_pitch + p * sh.cols_pitch + q];
@@ -152,16 +210,20 @@ static void fill_out_coef(const nova_transforms *t, OutCoef<N> &k)
 }
 
 template <int N, typename T>
-static size_t out_shape(int twb, OutShape &sh)
+static size_t out_shape(int twb, int trb, OutShape &sh)
 {
     constexpr int M = N - 2;
-    sh.twb = twb;
+    sh.twb = twb * trb;
+    sh.trb = trb;
+    sh.rows = trb * M;
+    sh.rows_magic = (unsigned)((((unsigned long long)1 << 32) + sh.rows - 1) / sh.rows);
     sh.cols_pitch = (twb * M + 3) / 4 * 4;              // rows stay 8-byte aligned
-    int kp = M * sh.cols_pitch;                         // multiple of 4
+    int kp = sh.rows * sh.cols_pitch;                   // multiple of 4
     // channel pitch 4 * odd elements: 8-byte aligned rows, and the 32 channels of a half-wave
     // writing one (row, column) fall into different banks
     if ((kp / 4) % 2 == 0) kp += 4;
     sh.k_pitch = kp;
+    sh.pieces = 1; sh.piece_magic = 0; sh.w_magic = 0;
     return (size_t)kChanBlock * kp * sizeof(T);
 }
 
@@ -175,25 +237,45 @@ static int launch_ot(const nova_transforms *t, const void *Mp, void *y, const Ge
     fill_out_coef<N>(t, coef);
     OutShape sh;
     int twb_max = 16;
-    while (twb_max > 1 && out_shape<N, T>(twb_max, sh) > 64 * 1024) --twb_max;
+    while (twb_max > 1 && out_shape<N, T>(twb_max, 1, sh) > 64 * 1024) --twb_max;
     sh.groups = ceil_div(g.tiles_w, twb_max);
-    const int twb = ceil_div(g.tiles_w, sh.groups);
-    const size_t lds_bytes = out_shape<N, T>(twb, sh);
+    const int twb = ceil_div(g.tiles_w, sh.groups);     // tiles of one tile row per group
+    // narrow images: a group spans the width; give it as many tile rows as keep it within 8 tiles
+    // (more per workgroup measured slower: 56 x 56 with 2 x 7 tiles 42 us against 39 us with 7)
+    int trb = 1;
+    if (sh.groups == 1) {
+        trb = 8 / twb;
+        if (trb < 1) trb = 1;
+        if (trb > g.tiles_h) trb = g.tiles_h;
+        while (trb > 1 && out_shape<N, T>(twb, trb, sh) > 64 * 1024) --trb;
+    }
+    trb = ceil_div(g.tiles_h, ceil_div(g.tiles_h, trb));    // same number of groups, evenly sized
+    const size_t lds_bytes = out_shape<N, T>(twb, trb, sh);     // (leaves sh.groups alone)
     if (lds_bytes > 64 * 1024) return (int)hipErrorInvalidValue;
     if ((size_t)g.k_blocks * g.Tp * kChanBlock * sizeof(MT) >= ((size_t)1 << 32)) return (int)hipErrorInvalidValue;
-    const bool vec = g.W % PE == 0 && ((uintptr_t)y % 16) == 0 && (sh.groups == 1 || (twb * M) % PE == 0);
-    const int threads = ((twb * 32 + 63) / 64) * 64;
-    const long long blocks = (long long)sh.groups * g.tiles_h * g.k_blocks * g.N;
+    const bool aligned = ((uintptr_t)y % 16) == 0;
+    const bool vec = g.W % PE == 0 && aligned && (sh.groups == 1 || (twb * M) % PE == 0);
+    const bool flat = !vec && aligned && sh.groups == 1 && (long long)sh.rows * g.W < (1 << 15);
+    if (flat) {
+        sh.pieces = (sh.rows * g.W + 2 * (PE - 1)) / PE;
+        sh.piece_magic = (unsigned)((((unsigned long long)1 << 32) + sh.pieces - 1) / sh.pieces);
+        sh.w_magic = (unsigned)((((unsigned long long)1 << 32) + g.W - 1) / g.W);
+    }
+    const int threads = ((sh.twb * 32 + 63) / 64) * 64;
+    const long long blocks = (long long)sh.groups * ceil_div(g.tiles_h, trb) * g.k_blocks * g.N;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
     void (*kern)(const MT *, T *, int, int, int, int, int, int, long long, OutShape, OutCoef<N>);
     const bool relu = (flags & NOVA_FLAG_RELU) != 0;
-    if (t->symmetric) {
-        if (vec) kern = relu ? output_transform_kernel<N, T, MT, true, true, true> : output_transform_kernel<N, T, MT, true, true, false>;
-        else     kern = relu ? output_transform_kernel<N, T, MT, true, false, true> : output_transform_kernel<N, T, MT, true, false, false>;
-    } else {
-        if (vec) kern = relu ? output_transform_kernel<N, T, MT, false, true, true> : output_transform_kernel<N, T, MT, false, true, false>;
-        else     kern = relu ? output_transform_kernel<N, T, MT, false, false, true> : output_transform_kernel<N, T, MT, false, false, false>;
-    }
+    const int stg = vec ? kStoreVec : flat ? kStoreFlat : kStoreScalar;
+    auto pick = [&](auto sym) {
+        constexpr bool S = decltype(sym)::value;
+        switch (stg) {
+        case kStoreVec:  return relu ? output_transform_kernel<N, T, MT, S, kStoreVec, true> : output_transform_kernel<N, T, MT, S, kStoreVec, false>;
+        case kStoreFlat: return relu ? output_transform_kernel<N, T, MT, S, kStoreFlat, true> : output_transform_kernel<N, T, MT, S, kStoreFlat, false>;
+        default:         return relu ? output_transform_kernel<N, T, MT, S, kStoreScalar, true> : output_transform_kernel<N, T, MT, S, kStoreScalar, false>;
+        }
+    };
+    kern = t->symmetric ? pick(std::true_type{}) : pick(std::false_type{});
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds_bytes, stream,
                        (const MT *)Mp, (T *)y, g.K, g.H, g.W, g.tiles_h, g.tiles_w, g.k_blocks, g.Tp, sh, coef);
     return (int)hipGetLastError();

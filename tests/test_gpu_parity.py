@@ -88,6 +88,9 @@ SMALL_FP16 = [
     ("nova", 6, 2, 40, 130, 56, 56),
     ("nova", 8, 3, 72, 96, 56, 56),
     ("nova", 8, 1, 3, 5, 17, 70),
+    # narrow images of odd size: strips staged from unaligned runs, x not a whole number of 16-byte pieces
+    ("nova", 4, 1, 3, 5, 7, 9),
+    ("nova", 6, 3, 35, 40, 13, 21),
     # shapes that take the weight-stationary contraction (C in {64,128,256}, K a multiple of 64),
     # one per (waves along K, channel blocks) variant, with ragged last stages
     ("nova", 4, 2, 64, 64, 20, 20),
@@ -155,6 +158,25 @@ def test_fp32_other_tiles(name, m):
     err = rel_l2(got["y"], y_o)
     say(f"  emulation vs definition {own:.3e}; gpu vs emulation {err:.3e}; gpu vs definition {rel_l2(got['y'], want):.3e}")
     assert err <= max(1e-5, 4 * own)
+
+
+@pytest.mark.parametrize("m", [4, 6, 8])
+def test_fp32_narrow_images(m):
+    # few tiles per tile row: workgroups take several tile rows, strips come from unaligned runs
+    say(f"[case] fp32 narrow image F({m},3)")
+    points = synth.point_set("nova", m)
+    x, w = synth.make_layer(3, 9, 33, 2 * m + 3, 2 * m + 1, seed=70 + m, dtype="f32", x_dist="normal")
+    t = nova.nova_make_transforms(points, m, 3)
+    got = run_stages(t, x, w)
+    x64, w64 = x.astype(np.float64), w.astype(np.float64)
+    y_o, U_o, V_o, M_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=32, want_intermediates=True)
+    same(got["U"], U_o, "U")
+    same(got["V"], V_o, "V")
+    own = rel_l2(y_o, conv.direct_conv2d(x64, w64))
+    err = rel_l2(got["y"], y_o)
+    say(f"  emulation vs definition {own:.3e}; gpu vs emulation {err:.3e}")
+    assert err <= max(1e-5, 4 * own)
+    assert np.array_equal(got["y"], got["y_conv"])
 
 
 def test_generic_point_order_uses_the_same_contract():
