@@ -103,14 +103,30 @@ def winograd_conv2d_f64(x, g, points, m):
     return y
 
 
+def _matrices(points, m, row_scaling):
+    A, BT, G = ct.cook_toom(points, m, 3)
+    if row_scaling is None:
+        return A, BT, G
+    if isinstance(row_scaling, str):
+        if row_scaling != "balanced":
+            raise ValueError(row_scaling)
+        log2_b, log2_g = ct.balanced_row_exponents(BT, G)
+    else:
+        log2_b, log2_g = row_scaling
+    return ct.scale_rows(A, BT, G, log2_b, log2_g)
+
+
 def winograd_conv2d_emulated(x, g, points, m, storage=16, m_storage=32, v_exact=False,
-                             relu=False, transform_dtype="f32", want_intermediates=False):
+                             relu=False, transform_dtype="f32", want_intermediates=False,
+                             row_scaling=None):
     """Winograd with the intermediate tensors rounded as the fp16 (storage=16) or fp32
     (storage=32) device path rounds them.  x and g must already be exact in the storage
     format.  transform_dtype 'f32' keeps A and B^T as binary32 constants, 'f16' first rounds
     every matrix entry to binary16 ("matrices stored in float16").
+    row_scaling: None, "balanced", or (log2_b, log2_g) -- power-of-two row scales applied to
+    the exact matrices before any rounding (cook_toom.scale_rows).
     Returns y, or (y, U, V, M) with U [n*n,K,C], V [n*n,T,C], M [n*n,T,K] as fp64."""
-    A, BT, G = ct.cook_toom(points, m, 3)
+    A, BT, G = _matrices(points, m, row_scaling)
     if transform_dtype == "f32":
         A32, BT32, G64 = ct.to_f32(A), ct.to_f32(BT), ct.to_f64(G)
     elif transform_dtype == "f16":

@@ -107,6 +107,53 @@ def rank_one_terms(A, BT, G):
     return terms
 
 
+def scale_rows(A, BT, G, log2_b, log2_g):
+    """Diagonal rescaling of the three matrices by powers of two, exactly.
+
+    The "learned diagonal scales" form discussed with the related work,
+        Y = D_A A^T [ (D_G G g) * (D_B B^T d) ],
+    restricted to the case that keeps the algorithm exact: row p of B^T is
+    multiplied by 2**log2_b[p], row p of G by 2**log2_g[p], and row p of A by
+    2**-(log2_b[p] + log2_g[p]), so the three factors of every row multiply to
+    one and the rank-one terms (hence the bilinear identity) are unchanged.
+    Only the range of the intermediate tensors U and V moves.
+    """
+    n = len(A)
+    if len(log2_b) != n or len(log2_g) != n:
+        raise ValueError("one exponent per row of B^T and of G is needed")
+    two = Fraction(2)
+    A2 = [[entry * two ** -(int(log2_b[p]) + int(log2_g[p])) for entry in A[p]] for p in range(n)]
+    BT2 = [[entry * two ** int(log2_b[p]) for entry in BT[p]] for p in range(n)]
+    G2 = [[entry * two ** int(log2_g[p]) for entry in G[p]] for p in range(n)]
+    return A2, BT2, G2
+
+
+def _balancing_exponent(row):
+    """The integer e with 1 <= 2**e * sum|row| < 2, found by exact comparisons."""
+    norm = sum(abs(entry) for entry in row)
+    if norm == 0:
+        raise ValueError("a transform row cannot vanish")
+    e = 0
+    while norm * Fraction(2) ** e >= 2:
+        e -= 1
+    while norm * Fraction(2) ** e < 1:
+        e += 1
+    return e
+
+
+def balanced_row_exponents(BT, G):
+    """Exponents (log2_b, log2_g) for `scale_rows` that bring the absolute row
+    sums of B^T and of G into [1, 2).
+
+    With them |V[(i,j)]| <= 4 max|d| and |U[(i,j)]| <= 4 max|g| for every
+    position (i, j) of the 2D transforms, whatever the points: the dynamic range
+    of the stored tensors no longer depends on the magnitude of the Lagrange
+    factors.  (The paper's comparison uses learned scales; this fixed rule is
+    the exact, data-free member of the same family.)
+    """
+    return [_balancing_exponent(row) for row in BT], [_balancing_exponent(row) for row in G]
+
+
 def vandermonde(points):
     """Square Vandermonde matrix of the finite points, V[i][j] = alpha_i^j
     (Sec. 2.2; the point at infinity does not enter)."""

@@ -229,7 +229,7 @@ __device__ __forceinline__ void stream_wait_stage(int i)
 // throttle the issuing wave when HBM writes back up.
 template <int WN, int WM, int NB, int CB, int S, int OCC, typename MT>
 // (the second launch bound is waves per SIMD: a workgroup puts WN*WM/4 on each)
-__global__ void __launch_bounds__(64 * WN * WM, OCC * WN * WM / 4)
+__global__ void __launch_bounds__(64 * WN * WM, (OCC * WN * WM + 3) / 4)
 contract_stream_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__restrict__ Mo,
                        int T, int Tp, int Kp, int k_blocks, int stages_per_xi, int xi_count, int items_total, int wgs_per_seg)
 {
@@ -477,7 +477,9 @@ static int launch_c16_tiled(const void *U, const void *V, void *Mo, const Geomet
 template <typename MT>
 static int launch_c16_shape(const void *U, const void *V, void *Mo, const Geometry &g, hipStream_t s)
 {
-    // streaming kernel: C in {64, 128, 256} and K a multiple of the workgroup's channel span;
+    // streaming kernel: C in {64, 128, 256} and K a multiple of the workgroup's channel span
+    // (C = 512 variants, 16 channel blocks in 128 fragment registers at one workgroup per CU, measured
+    // no faster than the tiled kernel at T = 512 and slower at T = 128);
     // ring depth S: as many stages as fit about 128 KiB of LDS, at most 8
     const int cb = g.c_blocks;
     const int wn = g.Kp % 256 == 0 ? 4 : g.Kp % 128 == 0 ? 2 : g.Kp % 64 == 0 ? 1 : 0;

@@ -101,6 +101,10 @@ SMALL_FP16 = [
     ("nova", 4, 1, 128, 64, 64, 64),
     ("standard", 4, 1, 256, 512, 16, 16),
     ("nova", 8, 1, 128, 256, 17, 17),
+    # C = 512 (tiled contraction), K = 512 / 128 / 64
+    ("nova", 8, 5, 512, 512, 24, 24),
+    ("nova", 6, 2, 512, 128, 13, 13),
+    ("nova", 4, 1, 512, 64, 12, 20),
 ]
 
 

@@ -238,6 +238,48 @@ def test_integer_point_f83_overflows_binary16():
     assert np.isfinite(y_nova).all()
 
 
+def test_row_scaling_by_powers_of_two_is_exact_where_nothing_overflows():
+    # F(4,3), integer points, data as in the exactness test above: every intermediate is an exact
+    # binary16 number with and without scaling (scaling by 2^e moves exponents only), so the scaled
+    # run must reproduce the unscaled one bit for bit, and U, V must be the unscaled ones times the
+    # row factors.
+    rng = np.random.default_rng(9)
+    x = rng.integers(-1, 2, size=(1, 2, 8, 9)).astype(np.float64)
+    g = 576.0 * rng.integers(-1, 2, size=(2, 2, 3, 3)).astype(np.float64)
+    points = pts(synth.STANDARD[4])
+    y0, U0, V0, _ = conv.winograd_conv2d_emulated(x, g, points, 4, storage=16, want_intermediates=True)
+    A, BT, G = ct.cook_toom(points, 4, 3)
+    log2_b, log2_g = ct.balanced_row_exponents(BT, G)
+    for scaling in ("balanced", (log2_b, log2_g)):
+        y1, U1, V1, _ = conv.winograd_conv2d_emulated(x, g, points, 4, storage=16, row_scaling=scaling,
+                                                      want_intermediates=True)
+        assert np.array_equal(y1, y0)
+        fb = np.array([2.0 ** (log2_b[i] + log2_b[j]) for i in range(6) for j in range(6)])
+        fg = np.array([2.0 ** (log2_g[i] + log2_g[j]) for i in range(6) for j in range(6)])
+        assert np.array_equal(V1, V0 * fb[:, None, None])
+        assert np.array_equal(U1, U0 * fg[:, None, None])
+
+
+def test_balanced_rows_make_integer_point_f83_finite():
+    # range, not conditioning: with balanced rows the integer-point F(8,3) intermediates fit
+    # binary16 (|V| <= 4 max|x|), the result is finite -- and still as inaccurate as kappa says,
+    # while the discovered points are far better with or without scaling ("methods are
+    # orthogonal", Table "Network-level ablation: points x scaling")
+    x, g = synth.make_layer(1, 16, 4, 16, 16, seed=5, dtype="f16")
+    x64, g64 = x.astype(np.float64), g.astype(np.float64)
+    want = conv.direct_conv2d(x64, g64)
+    y, U, V, M = conv.winograd_conv2d_emulated(x64, g64, pts(synth.STANDARD[8]), 8, storage=16,
+                                               row_scaling="balanced", want_intermediates=True)
+    assert np.isfinite(V).all() and np.isfinite(U).all() and np.isfinite(y).all()
+    assert np.abs(V).max() <= 4 * np.abs(x64).max()
+    e_std = rel_l2(y, want)
+    e_nova = rel_l2(conv.winograd_conv2d_emulated(x64, g64, pts(synth.NOVA[8]), 8, storage=16), want)
+    e_nova_bal = rel_l2(conv.winograd_conv2d_emulated(x64, g64, pts(synth.NOVA[8]), 8, storage=16,
+                                                     row_scaling="balanced"), want)
+    assert e_std > 5 * e_nova
+    assert 0.5 * e_nova < e_nova_bal < 2.0 * e_nova
+
+
 def test_emulated_relu_and_transform_dtype_option():
     points = pts(synth.NOVA[4])
     x, g = synth.make_layer(1, 8, 4, 9, 9, seed=6, dtype="f16", x_dist="normal")

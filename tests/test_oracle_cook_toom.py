@@ -173,6 +173,63 @@ def test_f43_matrices_equal_textbook_entrywise(golden_dir):
     assert (A, BT, G) == (book["A"], book["BT"], book["G"])
 
 
+# ---------------------------------------------------------------- power-of-two row scaling
+
+
+def test_row_scaling_leaves_the_algorithm_unchanged():
+    # any integer exponents: rank-one terms, identity and the exact 1D result stay what they were
+    rng = random.Random(11)
+    for key in sorted(SETS):
+        m = key[1]
+        A, BT, G = ct.cook_toom(SETS[key], m, 3)
+        n = m + 2
+        log2_b = [rng.randint(-9, 9) for _ in range(n)]
+        log2_g = [rng.randint(-9, 9) for _ in range(n)]
+        A2, BT2, G2 = ct.scale_rows(A, BT, G, log2_b, log2_g)
+        assert ct.rank_one_terms(A2, BT2, G2) == ct.rank_one_terms(A, BT, G)
+        assert ct.tensor_identity_holds(A2, BT2, G2)
+        x = [Fr(rng.randint(-50, 50), rng.randint(1, 7)) for _ in range(n)]
+        g = [Fr(rng.randint(-50, 50), rng.randint(1, 7)) for _ in range(3)]
+        assert exact.winograd_1d(x, g, A2, BT2, G2) == [sum(g[k] * x[i + k] for k in range(3)) for i in range(m)]
+        # and the scale really sits where it was asked for
+        for p in range(n):
+            assert BT2[p] == [e * Fr(2) ** log2_b[p] for e in BT[p]]
+            assert G2[p] == [e * Fr(2) ** log2_g[p] for e in G[p]]
+
+
+def test_balanced_rows_hand_worked_f43(golden_dir):
+    rows = read_rows(os.path.join(golden_dir, "balanced_rows_f43_textbook.txt"))
+    want = {}
+    for row in rows:
+        if row[0] in ("log2_b", "log2_g"):
+            want[row[0]] = [int(v) for v in row[1:]]
+        else:
+            want[row[0]] = [[Fr(v) for v in part.split()] for part in " ".join(row[1:]).split(";")]
+    A, BT, G = ct.cook_toom(SETS[("std", 4)], 4, 3)
+    log2_b, log2_g = ct.balanced_row_exponents(BT, G)
+    assert (log2_b, log2_g) == (want["log2_b"], want["log2_g"])
+    assert ct.scale_rows(A, BT, G, log2_b, log2_g) == (want["A"], want["BT"], want["G"])
+
+
+@pytest.mark.parametrize("key", sorted(SETS))
+def test_balanced_rows_bound_the_row_sums(key):
+    m = key[1]
+    A, BT, G = ct.cook_toom(SETS[key], m, 3)
+    log2_b, log2_g = ct.balanced_row_exponents(BT, G)
+    _, BT2, G2 = ct.scale_rows(A, BT, G, log2_b, log2_g)
+    for row in BT2 + G2:
+        assert 1 <= sum(abs(e) for e in row) < 2
+    # rows of +a and -a get the same exponent (their entries differ in sign only)
+    for p in range(1, m + 1, 2):
+        assert log2_b[p] == log2_b[p + 1] and log2_g[p] == log2_g[p + 1]
+
+
+def test_scale_rows_rejects_wrong_lengths():
+    A, BT, G = ct.cook_toom(SETS[("std", 2)], 2, 3)
+    with pytest.raises(ValueError):
+        ct.scale_rows(A, BT, G, [0, 0, 0], [0, 0, 0, 0])
+
+
 # ---------------------------------------------------------------- float tables
 
 
