@@ -75,6 +75,39 @@ enum {
  */
 int nova_make_transforms(const nova_rational *finite_points, int n_points, int m, int r,
                          nova_transforms **out);
+
+/*
+ * The same construction with two options.
+ *
+ * row_scaling -- the diagonal-scale form Y = D_A A^T [ (D_G G g) . (D_B B^T d) ] (related-work
+ * discussion of learned diagonal scales; Table "Network-level ablation: points x scaling"),
+ * restricted to powers of two with D_A D_G D_B = I, so the algorithm stays exact and only the range
+ * of U and V moves:  row p of B^T is multiplied by 2^log2_b[p], row p of G by 2^log2_g[p], row p
+ * of A by 2^-(log2_b[p] + log2_g[p]).
+ *   NOVA_ROWS_PLAIN     no scaling (log2_b, log2_g ignored, may be NULL)
+ *   NOVA_ROWS_BALANCED  the exponents that bring the absolute row sums of B^T and of G into
+ *                       [1, 2): then |V| <= 4 max|x| and |U| <= 4 max|w| whatever the points
+ *   NOVA_ROWS_GIVEN     log2_b, log2_g: host arrays of n = m + r - 1 exponents, each in [-60, 60]
+ * The scaled matrices are verified against the exact identity again.  The device transforms share
+ * work between the rows of +a and -a only if both rows carry the same exponents (always so for
+ * NOVA_ROWS_BALANCED); otherwise the general kernels run.
+ *
+ * matrix_dtype -- what the device constants are rounded to (each entry once, from the exact value):
+ *   NOVA_MATRIX_F32  A, B^T binary32, G binary64 (the default of nova_make_transforms)
+ *   NOVA_MATRIX_F16  every entry to the nearest binary16 first ("matrices stored in float16",
+ *                    Table "FP16 storage"); the rounded tables then hold those values
+ * Errors as nova_make_transforms, plus NOVA_EINVAL for an unknown option or exponent out of range.
+ */
+#define NOVA_ROWS_PLAIN 0
+#define NOVA_ROWS_BALANCED 1
+#define NOVA_ROWS_GIVEN 2
+#define NOVA_MATRIX_F32 0
+#define NOVA_MATRIX_F16 1
+int nova_make_transforms_ex(const nova_rational *finite_points, int n_points, int m, int r,
+                            int row_scaling, const int *log2_b, const int *log2_g, int matrix_dtype,
+                            nova_transforms **out);
+/* The exponents in effect (all zero for NOVA_ROWS_PLAIN): n entries each, either may be NULL. */
+int nova_get_row_scaling(const nova_transforms *t, int *log2_b, int *log2_g);
 void nova_free_transforms(nova_transforms *t);
 
 /* m, r, n of a handle; `symmetric` = 1 when the points come as 0, +a1, -a1, +a2, -a2, ...

@@ -33,13 +33,15 @@ struct InCoef {
 };
 
 // Coefficients of one 1D output transform: A (N x M) row-major, and for the symmetric case
-// pw[j][i] = a_j^i.
+// pw[j][i] = A[row of +a_j][i] (a_j^i times the row's scale), zero = A[row of 0][0],
+// inf = A[row of infinity][M-1] (both 1 unless the rows are rescaled).
 template <int N>
 struct OutCoef {
     static constexpr int M = N - 2;
     static constexpr int H = (N - 2) / 2;
     float a[N * M];
     float pw[H > 0 ? H * M : 1];
+    float zero, inf;
 };
 
 template <int N>
@@ -79,6 +81,8 @@ inline size_t dtype_size(int dtype) { return dtype == NOVA_F16 ? 2 : 4; }
 struct nova_transforms {
     int m = 0, r = 0, n = 0;
     bool symmetric = false;
+    int matrix_dtype = 0;                      // NOVA_MATRIX_F32 / NOVA_MATRIX_F16
+    std::vector<int> log2_b, log2_g;           // row scaling in effect, n entries each
     std::vector<nova::Rat> points, A, BT, G;   // exact, row-major
     std::vector<double> A64, BT64, G64;        // rounded once
     std::vector<float> A32, BT32, G32;

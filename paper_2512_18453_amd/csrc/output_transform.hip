@@ -28,18 +28,19 @@ __device__ __forceinline__ void output_transform_1d(const float (&v)[N], float (
             s[j] = v[2 * j + 1] + v[2 * j + 2];
             d[j] = v[2 * j + 1] - v[2 * j + 2];
         }
-        float y0 = v[0];
+        // (with unscaled rows zero = inf = pw[j][0] = 1 and these are plain sums)
+        float y0 = k.zero * v[0];
 #pragma unroll
-        for (int j = 0; j < H; ++j) y0 += s[j];
+        for (int j = 0; j < H; ++j) y0 = fma32(k.pw[j * M], s[j], y0);
         out[0] = y0;
 #pragma unroll
         for (int i = 1; i < M; ++i) {
-            float acc = (i == M - 1) ? v[N - 1] : 0.0f;
+            float acc = (i == M - 1) ? k.inf * v[N - 1] : 0.0f;
 #pragma unroll
             for (int j = 0; j < H; ++j) acc = fma32(k.pw[j * M + i], (i & 1) ? d[j] : s[j], acc);
             out[i] = acc;
         }
-        if constexpr (M == 1) out[0] += v[N - 1];
+        if constexpr (M == 1) out[0] = fma32(k.inf, v[N - 1], out[0]);
     } else {
 #pragma unroll
         for (int i = 0; i < M; ++i) {
@@ -207,6 +208,8 @@ static void fill_out_coef(const nova_transforms *t, OutCoef<N> &k)
     for (int i = 0; i < N * M; ++i) k.a[i] = t->A32[i];
     for (int j = 0; j < H; ++j)
         for (int i = 0; i < M; ++i) k.pw[j * M + i] = t->A32[(2 * j + 1) * M + i];
+    k.zero = t->A32[0];
+    k.inf = t->A32[(N - 1) * M + (M - 1)];
 }
 
 template <int N, typename T>

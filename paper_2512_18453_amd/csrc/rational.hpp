@@ -102,6 +102,29 @@ inline double round_rat_to_bits(const Rat &a)
     return negative ? -v : v;
 }
 
+// Nearest binary16 value (ties to even) as a double: sub-normals below 2^-14 (multiples of
+// 2^-24) and overflow to infinity above the largest finite value included.
+// Requires |num|, den < 2^63.
+inline double rat_to_f16_value(const Rat &a)
+{
+    if (a.num == 0) return 0.0;
+    const bool negative = a.num < 0;
+    const u128 num = (u128)(negative ? -a.num : a.num), den = (u128)a.den;
+    double v;
+    if ((num << 14) < den) {                                 // |a| < 2^-14: fixed quantum 2^-24
+        const u128 q = (num << 24) / den, rem = (num << 24) % den;
+        u128 kept = q;
+        if (2 * rem > den || (2 * rem == den && (kept & 1))) ++kept;
+        v = std::ldexp((double)(uint64_t)kept, -24);
+    } else {
+        Rat mag = a;
+        mag.num = (i128)num;
+        v = round_rat_to_bits<11>(mag);
+        if (v > 65504.0) v = INFINITY;
+    }
+    return negative ? -v : v;
+}
+
 inline double rat_to_f64(const Rat &a) { return round_rat_to_bits<53>(a); }
 inline float rat_to_f32(const Rat &a) { return (float)round_rat_to_bits<24>(a); }
 

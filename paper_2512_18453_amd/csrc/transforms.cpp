@@ -113,14 +113,61 @@ const std::vector<Rat> *pick(const nova_transforms *t, int which, int *rows, int
 
 }  // namespace
 
+namespace {
+
+// the integer e with 1 <= 2^e * sum|row| < 2, by exact comparisons
+int balancing_exponent(RatCtx &cx, const Rat *row, int len)
+{
+    Rat norm = cx.make(0, 1);
+    for (int j = 0; j < len; ++j) {
+        Rat mag = row[j];
+        if (mag.num < 0) mag.num = -mag.num;
+        norm = cx.add(norm, mag);
+    }
+    if (!cx.ok || norm.num == 0) { cx.ok = false; return 0; }
+    // norm = num / den;  2^e * num >= den  and  2^e * num < 2 * den
+    int e = 0;
+    auto scaled_ge = [&](int ee, int factor) {           // 2^ee * num >= factor * den ?
+        nova::i128 lhs = norm.num, rhs = norm.den * factor;
+        if (ee >= 0) lhs = cx.mul(lhs, (nova::i128)1 << ee); else rhs = cx.mul(rhs, (nova::i128)1 << -ee);
+        return lhs >= rhs;
+    };
+    while (cx.ok && e > -120 && scaled_ge(e, 2)) --e;
+    while (cx.ok && e < 120 && !scaled_ge(e, 1)) ++e;
+    return e;
+}
+
+Rat times_pow2(RatCtx &cx, const Rat &v, int e)
+{
+    return e >= 0 ? cx.mul(v, cx.make((nova::i128)1 << e, 1)) : cx.mul(v, cx.make(1, (nova::i128)1 << -e));
+}
+
+}  // namespace
+
 extern "C" int nova_make_transforms(const nova_rational *finite_points, int n_points, int m, int r,
                                     nova_transforms **out)
+{
+    return nova_make_transforms_ex(finite_points, n_points, m, r, NOVA_ROWS_PLAIN, nullptr, nullptr,
+                                   NOVA_MATRIX_F32, out);
+}
+
+extern "C" int nova_make_transforms_ex(const nova_rational *finite_points, int n_points, int m, int r,
+                                       int row_scaling, const int *log2_b, const int *log2_g,
+                                       int matrix_dtype, nova_transforms **out)
 {
     if (!out) return NOVA_EINVAL;
     *out = nullptr;
     if (!finite_points || m < 1 || r < 1) return NOVA_EINVAL;
     const int n = m + r - 1;
     if (n > nova::kMaxN || n_points != n - 1) return NOVA_EINVAL;
+    if (row_scaling != NOVA_ROWS_PLAIN && row_scaling != NOVA_ROWS_BALANCED && row_scaling != NOVA_ROWS_GIVEN)
+        return NOVA_EINVAL;
+    if (matrix_dtype != NOVA_MATRIX_F32 && matrix_dtype != NOVA_MATRIX_F16) return NOVA_EINVAL;
+    if (row_scaling == NOVA_ROWS_GIVEN) {
+        if (!log2_b || !log2_g) return NOVA_EINVAL;
+        for (int p = 0; p < n; ++p)
+            if (log2_b[p] < -60 || log2_b[p] > 60 || log2_g[p] < -60 || log2_g[p] > 60) return NOVA_EINVAL;
+    }
 
     RatCtx cx;
     nova_transforms *t = new (std::nothrow) nova_transforms;
@@ -166,6 +213,31 @@ extern "C" int nova_make_transforms(const nova_rational *finite_points, int n_po
         return rc;
     }
 
+    // ---- optional power-of-two row scaling, exact, verified again
+    t->log2_b.assign(n, 0);
+    t->log2_g.assign(n, 0);
+    if (row_scaling != NOVA_ROWS_PLAIN) {
+        for (int p = 0; p < n; ++p) {
+            t->log2_b[p] = row_scaling == NOVA_ROWS_GIVEN ? log2_b[p] : balancing_exponent(cx, &t->BT[(size_t)p * n], n);
+            t->log2_g[p] = row_scaling == NOVA_ROWS_GIVEN ? log2_g[p] : balancing_exponent(cx, &t->G[(size_t)p * r], r);
+        }
+        if (!cx.ok) { delete t; return NOVA_EOVERFLOW; }
+        for (int p = 0; p < n; ++p) {
+            for (int j = 0; j < n; ++j) t->BT[(size_t)p * n + j] = times_pow2(cx, t->BT[(size_t)p * n + j], t->log2_b[p]);
+            for (int k = 0; k < r; ++k) t->G[(size_t)p * r + k] = times_pow2(cx, t->G[(size_t)p * r + k], t->log2_g[p]);
+            for (int i = 0; i < m; ++i) t->A[(size_t)p * m + i] = times_pow2(cx, t->A[(size_t)p * m + i], -(t->log2_b[p] + t->log2_g[p]));
+        }
+        if (!cx.ok) { delete t; return NOVA_EOVERFLOW; }
+        for (const std::vector<Rat> *mat : {&t->A, &t->BT, &t->G})
+            for (const Rat &e : *mat)
+                if (!RatCtx::fits64(e)) { delete t; return NOVA_EOVERFLOW; }
+        if (!identity_holds(cx, *t)) {
+            int rc = cx.ok ? NOVA_EVERIFY : NOVA_EOVERFLOW;
+            delete t;
+            return rc;
+        }
+    }
+
     // canonical symmetric order: 0, +a1, -a1, +a2, -a2, ...
     bool sym = (n - 1) % 2 == 1 && RatCtx::is_zero(t->points[0]);
     for (int j = 1; sym && j + 1 < n - 1; j += 2)
@@ -188,10 +260,40 @@ extern "C" int nova_make_transforms(const nova_rational *finite_points, int n_po
     }
     t->symmetric = sym;
 
-    for (const Rat &e : t->A) { t->A64.push_back(nova::rat_to_f64(e)); t->A32.push_back(nova::rat_to_f32(e)); }
-    for (const Rat &e : t->BT) { t->BT64.push_back(nova::rat_to_f64(e)); t->BT32.push_back(nova::rat_to_f32(e)); }
-    for (const Rat &e : t->G) { t->G64.push_back(nova::rat_to_f64(e)); t->G32.push_back(nova::rat_to_f32(e)); }
+    t->matrix_dtype = matrix_dtype;
+    auto fill = [&](const std::vector<Rat> &exact, std::vector<double> &t64, std::vector<float> &t32) {
+        for (const Rat &e : exact) {
+            if (matrix_dtype == NOVA_MATRIX_F16) {
+                const double v = nova::rat_to_f16_value(e);      // exact in binary32 and binary64
+                t64.push_back(v);
+                t32.push_back((float)v);
+            } else {
+                t64.push_back(nova::rat_to_f64(e));
+                t32.push_back(nova::rat_to_f32(e));
+            }
+        }
+    };
+    fill(t->A, t->A64, t->A32);
+    fill(t->BT, t->BT64, t->BT32);
+    fill(t->G, t->G64, t->G32);
+    if (matrix_dtype == NOVA_MATRIX_F16) {
+        // rounding may break what the paired kernels assume of the zero entries only if a non-zero
+        // entry rounds to zero or infinity; +a / -a rows round alike, so the pairing itself survives
+        for (const std::vector<double> *tab : {&t->A64, &t->BT64, &t->G64})
+            for (double v : *tab)
+                if (std::isinf(v)) { delete t; return NOVA_EOVERFLOW; }
+    }
     *out = t;
+    return NOVA_OK;
+}
+
+extern "C" int nova_get_row_scaling(const nova_transforms *t, int *log2_b, int *log2_g)
+{
+    if (!t) return NOVA_EINVAL;
+    for (int p = 0; p < t->n; ++p) {
+        if (log2_b) log2_b[p] = t->log2_b[p];
+        if (log2_g) log2_g[p] = t->log2_g[p];
+    }
     return NOVA_OK;
 }
 

@@ -13,13 +13,15 @@ import torch
 
 NOVA_F32, NOVA_F16 = 0, 1
 NOVA_MATRIX_A, NOVA_MATRIX_BT, NOVA_MATRIX_G = 0, 1, 2
+NOVA_ROWS_PLAIN, NOVA_ROWS_BALANCED, NOVA_ROWS_GIVEN = 0, 1, 2
+NOVA_MATRIX_F32, NOVA_MATRIX_F16 = 0, 1
 NOVA_FLAG_RELU, NOVA_FLAG_M_F16 = 1, 2
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnova.so")
 _lib = None
 
 EXPORTS = [
-    "nova_make_transforms", "nova_free_transforms", "nova_transforms_shape", "nova_get_matrix",
+    "nova_make_transforms", "nova_make_transforms_ex", "nova_get_row_scaling", "nova_free_transforms", "nova_transforms_shape", "nova_get_matrix",
     "nova_get_matrix_f64", "nova_get_matrix_f32", "nova_kappa", "nova_filter_bytes", "nova_input_bytes",
     "nova_product_bytes", "nova_filter_transform", "nova_conv2d_workspace_bytes", "nova_winograd_conv2d",
     "nova_input_transform", "nova_contract", "nova_output_transform", "nova_relu_maxpool2x2",
@@ -50,6 +52,8 @@ def lib():
         vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
         ip = ctypes.POINTER(ctypes.c_int)
         L.nova_make_transforms.argtypes = [ctypes.POINTER(nova_rational), i, i, i, ctypes.POINTER(vp)]
+        L.nova_make_transforms_ex.argtypes = [ctypes.POINTER(nova_rational), i, i, i, i, ip, ip, i, ctypes.POINTER(vp)]
+        L.nova_get_row_scaling.argtypes = [vp, ip, ip]
         L.nova_free_transforms.argtypes = [vp]
         L.nova_free_transforms.restype = None
         L.nova_transforms_shape.argtypes = [vp, ip, ip, ip, ip]
@@ -114,8 +118,7 @@ class Transforms:
             self.handle = None
 
 
-def nova_make_transforms(points, m, r=3):
-    """points: finite interpolation points as ints, Fractions or (num, den) pairs."""
+def _points_array(points):
     arr = (nova_rational * max(len(points), 1))()
     for idx, p in enumerate(points):
         if isinstance(p, tuple):
@@ -123,11 +126,43 @@ def nova_make_transforms(points, m, r=3):
         else:
             fr = Fraction(p)
             arr[idx].num, arr[idx].den = fr.numerator, fr.denominator
+    return arr
+
+
+def nova_make_transforms(points, m, r=3, row_scaling=None, matrix_dtype="f32"):
+    """points: finite interpolation points as ints, Fractions or (num, den) pairs.
+    row_scaling: None, "balanced" or (log2_b, log2_g); matrix_dtype: "f32" or "f16"
+    (nova_make_transforms_ex)."""
+    arr = _points_array(points)
     handle = ctypes.c_void_p()
-    _check(lib().nova_make_transforms(arr, len(points), m, r, ctypes.byref(handle)), "nova_make_transforms")
+    if row_scaling is None and matrix_dtype == "f32":
+        _check(lib().nova_make_transforms(arr, len(points), m, r, ctypes.byref(handle)), "nova_make_transforms")
+    else:
+        n = m + r - 1
+        mode, b_arr, g_arr = NOVA_ROWS_PLAIN, None, None
+        if isinstance(row_scaling, str):
+            if row_scaling != "balanced":
+                raise ValueError(row_scaling)
+            mode = NOVA_ROWS_BALANCED
+        elif row_scaling is not None:
+            log2_b, log2_g = row_scaling
+            if len(log2_b) != n or len(log2_g) != n:
+                raise ValueError("row_scaling needs one exponent per matrix row")
+            mode = NOVA_ROWS_GIVEN
+            b_arr, g_arr = (ctypes.c_int * n)(*log2_b), (ctypes.c_int * n)(*log2_g)
+        md = {"f32": NOVA_MATRIX_F32, "f16": NOVA_MATRIX_F16}[matrix_dtype]
+        _check(lib().nova_make_transforms_ex(arr, len(points), m, r, mode, b_arr, g_arr, md, ctypes.byref(handle)),
+               "nova_make_transforms_ex")
     mm, rr, nn, sym = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
     _check(lib().nova_transforms_shape(handle, mm, rr, nn, sym), "nova_transforms_shape")
     return Transforms(handle, mm.value, rr.value, nn.value, bool(sym.value))
+
+
+def nova_get_row_scaling(t):
+    """(log2_b, log2_g): the power-of-two row exponents in effect."""
+    b, g = (ctypes.c_int * t.n)(), (ctypes.c_int * t.n)()
+    _check(lib().nova_get_row_scaling(t.handle, b, g), "nova_get_row_scaling")
+    return list(b), list(g)
 
 
 def _matrix_shape(t, which):

@@ -232,6 +232,73 @@ def test_integer_point_f83_blows_up_identically():
     assert bad_o.mean() > 0.9 and (bad_gpu == bad_o).mean() > 0.99
 
 
+def test_balanced_rows_make_integer_point_f83_finite():
+    # same data as above, rows of B^T and G scaled by powers of two into [1, 2) (exact): nothing
+    # overflows any more, U and V agree bit for bit, the result is finite (and as inaccurate as the
+    # conditioning of the integer points makes it)
+    say("[case] integer-point F(8,3) with balanced power-of-two rows")
+    points = synth.point_set("standard", 8)
+    x, w = synth.make_layer(1, 32, 8, 24, 24, seed=5, dtype="f16")
+    t = nova.nova_make_transforms(points, 8, 3, row_scaling="balanced")
+    assert t.symmetric
+    got = run_stages(t, x, w)
+    x64, w64 = x.astype(np.float64), w.astype(np.float64)
+    y_o, U_o, V_o, M_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), 8, storage=16, row_scaling="balanced",
+                                                      want_intermediates=True)
+    same(got["U"], U_o, "U")
+    same(got["V"], V_o, "V")
+    assert np.isfinite(got["V"]).all() and np.abs(got["V"]).max() <= 4 * np.abs(x64).max()
+    assert rel_l2(got["M"], M_o) < 1e-5
+    # the output itself is so wrong (conditioning) that a few entries leave the binary16 range at
+    # the final store; those must be the same few on both sides
+    fin = np.isfinite(y_o)
+    assert fin.mean() > 0.99 and (np.isfinite(got["y"]) == fin).mean() > 0.999
+    both = fin & np.isfinite(got["y"])
+    err = rel_l2(got["y"][both], y_o[both])
+    want = conv.direct_conv2d(x64, w64)
+    say(f"  rel-L2 vs emulation {err:.3e}; vs fp64 definition {rel_l2(got['y'][both], want[both]):.3e}")
+    assert err < 5e-3
+
+
+def test_row_scaling_and_fp16_matrices_follow_the_emulation():
+    x, w = synth.make_layer(2, 24, 20, 17, 22, seed=31, dtype="f16")
+    x64, w64 = x.astype(np.float64), w.astype(np.float64)
+    # discovered points, balanced rows: paired kernels
+    for name, m in (("nova", 4), ("nova", 6), ("nova", 8)):
+        say(f"[case] balanced rows, {name} F({m},3)")
+        points = synth.point_set(name, m)
+        t = nova.nova_make_transforms(points, m, 3, row_scaling="balanced")
+        got = run_stages(t, x, w)
+        y_o, U_o, V_o, _ = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=16, row_scaling="balanced",
+                                                        want_intermediates=True)
+        same(got["U"], U_o, "U")
+        same(got["V"], V_o, "V")
+        assert rel_l2(got["y"], y_o) < 5e-3
+    # exponents that differ between the rows of +a and -a: general kernels
+    say("[case] unpaired row exponents, nova F(4,3)")
+    points = synth.point_set("nova", 4)
+    scaling = ([1, -2, 0, 3, 3, -1], [0, 2, 1, -3, 0, 2])
+    t = nova.nova_make_transforms(points, 4, 3, row_scaling=scaling)
+    assert not t.symmetric
+    got = run_stages(t, x, w)
+    y_o, U_o, V_o, _ = conv.winograd_conv2d_emulated(x64, w64, pts(points), 4, storage=16, row_scaling=scaling,
+                                                    want_intermediates=True)
+    same(got["U"], U_o, "U")
+    same(got["V"], V_o, "V")
+    assert rel_l2(got["y"], y_o) < 5e-3
+    # matrices stored in binary16 (Table "FP16 storage"), dyadic and discovered points
+    for name, m in (("dyadic", 4), ("nova", 6)):
+        say(f"[case] binary16 matrices, {name} F({m},3)")
+        points = synth.point_set(name, m)
+        t = nova.nova_make_transforms(points, m, 3, matrix_dtype="f16")
+        got = run_stages(t, x, w)
+        y_o, U_o, V_o, _ = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=16, transform_dtype="f16",
+                                                        want_intermediates=True)
+        same(got["U"], U_o, "U")
+        same(got["V"], V_o, "V")
+        assert rel_l2(got["y"], y_o) < 5e-3
+
+
 def test_slabs_and_workspace_errors():
     say("[case] slab loop and workspace checks")
     points = synth.point_set("nova", 4)

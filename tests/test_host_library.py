@@ -43,6 +43,47 @@ def test_matrices_equal_oracle_exactly(name, m):
         assert np.array_equal(np.array(nova.nova_get_matrix_f32(t, which), dtype=np.float32), ct.to_f32(mat))
 
 
+@pytest.mark.parametrize("name,m", ALL_SETS)
+def test_row_scaling_and_fp16_matrices_equal_oracle(name, m):
+    points = synth.point_set(name, m)
+    A, BT, G = ct.cook_toom([Fr(a, b) for a, b in points], m, 3)
+    log2_b, log2_g = ct.balanced_row_exponents(BT, G)
+    t = nova.nova_make_transforms(points, m, 3, row_scaling="balanced")
+    assert nova.nova_get_row_scaling(t) == (log2_b, log2_g)
+    assert t.symmetric
+    A2, BT2, G2 = ct.scale_rows(A, BT, G, log2_b, log2_g)
+    got = [nova.nova_get_matrix(t, w) for w in (nova.NOVA_MATRIX_A, nova.NOVA_MATRIX_BT, nova.NOVA_MATRIX_G)]
+    assert got == [A2, BT2, G2]
+    assert np.array_equal(np.array(nova.nova_get_matrix_f32(t, nova.NOVA_MATRIX_BT), dtype=np.float32), ct.to_f32(BT2))
+    # explicit exponents, different for the rows of +a and -a: exact, but no longer paired
+    rng = np.random.default_rng(m)
+    eb, eg = [int(v) for v in rng.integers(-5, 6, m + 2)], [int(v) for v in rng.integers(-5, 6, m + 2)]
+    if m >= 2:
+        eb[2] = eb[1] + 1
+    tg = nova.nova_make_transforms(points, m, 3, row_scaling=(eb, eg))
+    assert nova.nova_get_row_scaling(tg) == (eb, eg)
+    assert [nova.nova_get_matrix(tg, w) for w in (0, 1, 2)] == list(ct.scale_rows(A, BT, G, eb, eg))
+    assert not tg.symmetric
+    # plain handle reports zero exponents
+    assert nova.nova_get_row_scaling(nova.nova_make_transforms(points, m, 3)) == ([0] * (m + 2), [0] * (m + 2))
+    # matrices stored in binary16: every table holds the nearest binary16 of the exact entry
+    t16 = nova.nova_make_transforms(points, m, 3, matrix_dtype="f16")
+    for which, mat in [(nova.NOVA_MATRIX_A, A), (nova.NOVA_MATRIX_BT, BT), (nova.NOVA_MATRIX_G, G)]:
+        want = ct.to_f16(mat)
+        assert np.array_equal(np.array(nova.nova_get_matrix_f32(t16, which), dtype=np.float32), want.astype(np.float32))
+        assert np.array_equal(np.array(nova.nova_get_matrix_f64(t16, which)), want.astype(np.float64))
+        assert nova.nova_get_matrix(t16, which) == mat           # the exact matrices are untouched
+
+
+def test_fp16_matrix_rounding_covers_subnormals():
+    # G entries of wide integer point sets fall below 2^-14: 1/F_p = 1/40320 for F(8,3)
+    pts = synth.point_set("standard", 8)
+    G = ct.cook_toom([Fr(a, b) for a, b in pts], 8, 3)[2]
+    assert min(abs(e) for row in G for e in row if e != 0) < Fr(1, 2 ** 14)
+    t16 = nova.nova_make_transforms(pts, 8, 3, matrix_dtype="f16")
+    assert np.array_equal(np.array(nova.nova_get_matrix_f64(t16, nova.NOVA_MATRIX_G)), ct.to_f16(G).astype(np.float64))
+
+
 def test_other_shapes_and_orders():
     # r = 5 and unordered, non-symmetric points: accepted by the host construction
     pts = [Fr(1, 3), Fr(-2), Fr(0), Fr(5, 7), Fr(1), Fr(-1, 2), Fr(3, 2)]
@@ -97,6 +138,22 @@ def test_error_codes():
     t5 = nova.nova_make_transforms([0, 1, -1, 2, -2, 3, -3], 4, 5)
     assert L.nova_filter_transform(t5.handle, 1, 1, 1, 0, 1, None) == -6      # r = 5: host only
     assert L.nova_conv2d_workspace_bytes(1, 1, 1, 1, 1, 5, 0, 0, 0) == 0
+
+
+def test_extended_constructor_rejects_bad_options():
+    arr = nova._points_array(synth.point_set("standard", 4))
+    h = ctypes.c_void_p()
+    L = nova.lib()
+    ok_b = (ctypes.c_int * 6)(0, 0, 0, 0, 0, 0)
+    assert L.nova_make_transforms_ex(arr, 5, 4, 3, 7, None, None, 0, ctypes.byref(h)) == -1        # unknown scaling
+    assert L.nova_make_transforms_ex(arr, 5, 4, 3, 0, None, None, 9, ctypes.byref(h)) == -1        # unknown dtype
+    assert L.nova_make_transforms_ex(arr, 5, 4, 3, 2, None, ok_b, 0, ctypes.byref(h)) == -1        # exponents missing
+    big = (ctypes.c_int * 6)(0, 61, 0, 0, 0, 0)
+    assert L.nova_make_transforms_ex(arr, 5, 4, 3, 2, big, ok_b, 0, ctypes.byref(h)) == -1         # out of range
+    assert h.value is None
+    assert L.nova_make_transforms_ex(arr, 5, 4, 3, 2, ok_b, ok_b, 0, ctypes.byref(h)) == 0
+    assert L.nova_get_row_scaling(None, None, None) == -1
+    L.nova_free_transforms(h)
 
 
 def test_sizes_follow_documented_layouts():
