@@ -103,6 +103,28 @@ def winograd_conv2d_f64(x, g, points, m):
     return y
 
 
+def int8_matrix_tile_error(points, m, trials=100, seed=0):
+    """Mean relative L2 error of one F(m x m, 3 x 3) tile computed in fp64 with A, B^T and G each
+    quantised to INT8 per tensor (cook_toom.quantize_int8), against the directly computed
+    m x m correlation, over `trials` input tiles and kernels drawn uniformly from [-1, 1]
+    (Sec. "INT8 Convolution Error Validation": setup and Table "INT8 convolution error")."""
+    A, BT, G = ct.cook_toom(points, m, 3)
+    Aq, BTq, Gq = (ct.to_f64(ct.quantize_int8(mat)[0]) for mat in (A, BT, G))
+    rng = np.random.default_rng(seed)
+    n = m + 2
+    total = 0.0
+    for _ in range(trials):
+        d = rng.uniform(-1.0, 1.0, (n, n))
+        g = rng.uniform(-1.0, 1.0, (3, 3))
+        ref = np.zeros((m, m))
+        for a in range(3):
+            for b in range(3):
+                ref += g[a, b] * d[a:a + m, b:b + m]
+        y = Aq.T @ ((Gq @ g @ Gq.T) * (BTq @ d @ BTq.T)) @ Aq
+        total += np.linalg.norm(y - ref) / np.linalg.norm(ref)
+    return total / trials
+
+
 def _matrices(points, m, row_scaling):
     A, BT, G = ct.cook_toom(points, m, 3)
     if row_scaling is None:
@@ -122,7 +144,9 @@ def winograd_conv2d_emulated(x, g, points, m, storage=16, m_storage=32, v_exact=
     """Winograd with the intermediate tensors rounded as the fp16 (storage=16) or fp32
     (storage=32) device path rounds them.  x and g must already be exact in the storage
     format.  transform_dtype 'f32' keeps A and B^T as binary32 constants, 'f16' first rounds
-    every matrix entry to binary16 ("matrices stored in float16").
+    every matrix entry to binary16 ("matrices stored in float16"), 'int8' first quantises each
+    matrix to INT8 per tensor (cook_toom.quantize_int8; the de-quantised values are then held as
+    binary32 / binary64 constants).
     row_scaling: None, "balanced", or (log2_b, log2_g) -- power-of-two row scales applied to
     the exact matrices before any rounding (cook_toom.scale_rows).
     Returns y, or (y, U, V, M) with U [n*n,K,C], V [n*n,T,C], M [n*n,T,K] as fp64."""
@@ -133,6 +157,10 @@ def winograd_conv2d_emulated(x, g, points, m, storage=16, m_storage=32, v_exact=
         A32 = ct.to_f16(A).astype(np.float32)
         BT32 = ct.to_f16(BT).astype(np.float32)
         G64 = ct.to_f16(G).astype(np.float64)
+    elif transform_dtype == "int8":
+        A32 = ct.to_f32(ct.quantize_int8(A)[0])
+        BT32 = ct.to_f32(ct.quantize_int8(BT)[0])
+        G64 = ct.to_f64(ct.quantize_int8(G)[0])
     else:
         raise ValueError(transform_dtype)
     x, g = _c64(x), _c64(g)

@@ -154,6 +154,32 @@ def balanced_row_exponents(BT, G):
     return [_balancing_exponent(row) for row in BT], [_balancing_exponent(row) for row in G]
 
 
+def quantize_int8(matrix):
+    """Symmetric per-tensor INT8 quantisation of a matrix, exactly (Sec. "INT8 Convolution
+    Error Validation", Setup): scale s = max|entry| / 127, code = entry / s rounded to nearest
+    with ties to even and saturated to [-128, 127], value = code * s.
+    Returns (values, codes, s): the de-quantised matrix (Fractions), the integer codes and the
+    scale.  (With this scale the largest entry gets code +-127, so nothing saturates; the clamp
+    is part of the stated scheme.)"""
+    top = max(abs(entry) for row in matrix for entry in row)
+    if top == 0:
+        raise ValueError("cannot quantise a zero matrix")
+    s = top / 127
+    codes = []
+    for row in matrix:
+        out = []
+        for entry in row:
+            scaled = entry / s
+            lo = scaled.numerator // scaled.denominator          # floor
+            rem = scaled - lo
+            if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and lo % 2 != 0):
+                lo += 1
+            out.append(max(-128, min(127, lo)))
+        codes.append(out)
+    values = [[code * s for code in row] for row in codes]
+    return values, codes, s
+
+
 def vandermonde(points):
     """Square Vandermonde matrix of the finite points, V[i][j] = alpha_i^j
     (Sec. 2.2; the point at infinity does not enter)."""
