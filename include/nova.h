@@ -96,6 +96,12 @@ int nova_make_transforms(const nova_rational *finite_points, int n_points, int m
  *   NOVA_MATRIX_F32  A, B^T binary32, G binary64 (the default of nova_make_transforms)
  *   NOVA_MATRIX_F16  every entry to the nearest binary16 first ("matrices stored in float16",
  *                    Table "FP16 storage"); the rounded tables then hold those values
+ *   NOVA_MATRIX_INT8 each of A, B^T, G quantised symmetrically per tensor (Sec. "INT8 Convolution
+ *                    Error Validation"): scale s = max|entry| / 127, code = entry / s rounded to
+ *                    nearest (ties to even) and saturated to [-128, 127], both computed exactly;
+ *                    the rounded tables hold code * s (A, B^T to binary32, G to binary64).  This is
+ *                    the configuration that reproduces the paper's printed INT8 error table.
+ * The exact matrices (nova_get_matrix) are the unrounded ones in every case.
  * Errors as nova_make_transforms, plus NOVA_EINVAL for an unknown option or exponent out of range.
  */
 #define NOVA_ROWS_PLAIN 0
@@ -103,11 +109,15 @@ int nova_make_transforms(const nova_rational *finite_points, int n_points, int m
 #define NOVA_ROWS_GIVEN 2
 #define NOVA_MATRIX_F32 0
 #define NOVA_MATRIX_F16 1
+#define NOVA_MATRIX_INT8 2
 int nova_make_transforms_ex(const nova_rational *finite_points, int n_points, int m, int r,
                             int row_scaling, const int *log2_b, const int *log2_g, int matrix_dtype,
                             nova_transforms **out);
 /* The exponents in effect (all zero for NOVA_ROWS_PLAIN): n entries each, either may be NULL. */
 int nova_get_row_scaling(const nova_transforms *t, int *log2_b, int *log2_g);
+/* INT8 codes (row-major, caller-allocated) and scale of one matrix of a handle made with
+ * NOVA_MATRIX_INT8; NOVA_EINVAL for other handles.  *scale is s rounded to binary64. */
+int nova_get_matrix_int8(const nova_transforms *t, int which, int8_t *codes, double *scale);
 void nova_free_transforms(nova_transforms *t);
 
 /* m, r, n of a handle; `symmetric` = 1 when the points come as 0, +a1, -a1, +a2, -a2, ...

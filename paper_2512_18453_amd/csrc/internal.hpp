@@ -83,6 +83,8 @@ struct nova_transforms {
     bool symmetric = false;
     int matrix_dtype = 0;                      // NOVA_MATRIX_F32 / NOVA_MATRIX_F16
     std::vector<int> log2_b, log2_g;           // row scaling in effect, n entries each
+    std::vector<int8_t> Aq, BTq, Gq;           // NOVA_MATRIX_INT8: codes
+    double scale_q[3] = {0, 0, 0};             //                   and scales of A, B^T, G
     std::vector<nova::Rat> points, A, BT, G;   // exact, row-major
     std::vector<double> A64, BT64, G64;        // rounded once
     std::vector<float> A32, BT32, G32;

@@ -162,7 +162,8 @@ extern "C" int nova_make_transforms_ex(const nova_rational *finite_points, int n
     if (n > nova::kMaxN || n_points != n - 1) return NOVA_EINVAL;
     if (row_scaling != NOVA_ROWS_PLAIN && row_scaling != NOVA_ROWS_BALANCED && row_scaling != NOVA_ROWS_GIVEN)
         return NOVA_EINVAL;
-    if (matrix_dtype != NOVA_MATRIX_F32 && matrix_dtype != NOVA_MATRIX_F16) return NOVA_EINVAL;
+    if (matrix_dtype != NOVA_MATRIX_F32 && matrix_dtype != NOVA_MATRIX_F16 && matrix_dtype != NOVA_MATRIX_INT8)
+        return NOVA_EINVAL;
     if (row_scaling == NOVA_ROWS_GIVEN) {
         if (!log2_b || !log2_g) return NOVA_EINVAL;
         for (int p = 0; p < n; ++p)
@@ -273,9 +274,42 @@ extern "C" int nova_make_transforms_ex(const nova_rational *finite_points, int n
             }
         }
     };
-    fill(t->A, t->A64, t->A32);
-    fill(t->BT, t->BT64, t->BT32);
-    fill(t->G, t->G64, t->G32);
+    if (matrix_dtype == NOVA_MATRIX_INT8) {
+        // per tensor: s = max|entry| / 127, code = round-half-even(entry / s), value = code * s, all exact
+        auto quantise = [&](const std::vector<Rat> &exact, std::vector<int8_t> &codes, double &scale,
+                            std::vector<double> &t64, std::vector<float> &t32) {
+            Rat top = cx.make(0, 1);
+            for (const Rat &e : exact) {
+                Rat mag = e;
+                if (mag.num < 0) mag.num = -mag.num;
+                if (mag.num * top.den > top.num * mag.den) top = mag;       // entries fit 64 bits: no overflow
+            }
+            const Rat s = cx.mul(top, cx.make(1, 127));
+            scale = nova::rat_to_f64(s);
+            for (const Rat &e : exact) {
+                const Rat scaled = cx.mul(e, cx.inv(s));                    // in [-127, 127]
+                nova::i128 lo = scaled.num / scaled.den;                    // truncates toward zero
+                if (scaled.num < 0 && lo * scaled.den != scaled.num) --lo;  // floor
+                const nova::i128 rem2 = 2 * (scaled.num - lo * scaled.den); // 2 * fractional part * den
+                if (rem2 > scaled.den || (rem2 == scaled.den && (lo % 2 != 0))) ++lo;
+                if (lo > 127) lo = 127;
+                if (lo < -128) lo = -128;
+                codes.push_back((int8_t)lo);
+                const Rat value = cx.mul(cx.make(lo, 1), s);
+                if (!cx.ok || !RatCtx::fits64(value)) { cx.ok = false; return; }
+                t64.push_back(nova::rat_to_f64(value));
+                t32.push_back(nova::rat_to_f32(value));
+            }
+        };
+        quantise(t->A, t->Aq, t->scale_q[0], t->A64, t->A32);
+        quantise(t->BT, t->BTq, t->scale_q[1], t->BT64, t->BT32);
+        quantise(t->G, t->Gq, t->scale_q[2], t->G64, t->G32);
+        if (!cx.ok) { delete t; return NOVA_EOVERFLOW; }
+    } else {
+        fill(t->A, t->A64, t->A32);
+        fill(t->BT, t->BT64, t->BT32);
+        fill(t->G, t->G64, t->G32);
+    }
     if (matrix_dtype == NOVA_MATRIX_F16) {
         // rounding may break what the paired kernels assume of the zero entries only if a non-zero
         // entry rounds to zero or infinity; +a / -a rows round alike, so the pairing itself survives
@@ -294,6 +328,17 @@ extern "C" int nova_get_row_scaling(const nova_transforms *t, int *log2_b, int *
         if (log2_b) log2_b[p] = t->log2_b[p];
         if (log2_g) log2_g[p] = t->log2_g[p];
     }
+    return NOVA_OK;
+}
+
+extern "C" int nova_get_matrix_int8(const nova_transforms *t, int which, int8_t *codes, double *scale)
+{
+    if (!t || t->matrix_dtype != NOVA_MATRIX_INT8 || !codes || !scale) return NOVA_EINVAL;
+    const std::vector<int8_t> *src = which == NOVA_MATRIX_A ? &t->Aq : which == NOVA_MATRIX_BT ? &t->BTq
+                                   : which == NOVA_MATRIX_G ? &t->Gq : nullptr;
+    if (!src) return NOVA_EINVAL;
+    std::copy(src->begin(), src->end(), codes);
+    *scale = t->scale_q[which];
     return NOVA_OK;
 }
 

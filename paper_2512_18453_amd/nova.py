@@ -14,14 +14,14 @@ import torch
 NOVA_F32, NOVA_F16 = 0, 1
 NOVA_MATRIX_A, NOVA_MATRIX_BT, NOVA_MATRIX_G = 0, 1, 2
 NOVA_ROWS_PLAIN, NOVA_ROWS_BALANCED, NOVA_ROWS_GIVEN = 0, 1, 2
-NOVA_MATRIX_F32, NOVA_MATRIX_F16 = 0, 1
+NOVA_MATRIX_F32, NOVA_MATRIX_F16, NOVA_MATRIX_INT8 = 0, 1, 2
 NOVA_FLAG_RELU, NOVA_FLAG_M_F16 = 1, 2
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnova.so")
 _lib = None
 
 EXPORTS = [
-    "nova_make_transforms", "nova_make_transforms_ex", "nova_get_row_scaling", "nova_free_transforms", "nova_transforms_shape", "nova_get_matrix",
+    "nova_make_transforms", "nova_make_transforms_ex", "nova_get_row_scaling", "nova_get_matrix_int8", "nova_free_transforms", "nova_transforms_shape", "nova_get_matrix",
     "nova_get_matrix_f64", "nova_get_matrix_f32", "nova_kappa", "nova_filter_bytes", "nova_input_bytes",
     "nova_product_bytes", "nova_filter_transform", "nova_conv2d_workspace_bytes", "nova_winograd_conv2d",
     "nova_input_transform", "nova_contract", "nova_output_transform", "nova_relu_maxpool2x2",
@@ -54,6 +54,7 @@ def lib():
         L.nova_make_transforms.argtypes = [ctypes.POINTER(nova_rational), i, i, i, ctypes.POINTER(vp)]
         L.nova_make_transforms_ex.argtypes = [ctypes.POINTER(nova_rational), i, i, i, i, ip, ip, i, ctypes.POINTER(vp)]
         L.nova_get_row_scaling.argtypes = [vp, ip, ip]
+        L.nova_get_matrix_int8.argtypes = [vp, i, ctypes.POINTER(ctypes.c_int8), ctypes.POINTER(ctypes.c_double)]
         L.nova_free_transforms.argtypes = [vp]
         L.nova_free_transforms.restype = None
         L.nova_transforms_shape.argtypes = [vp, ip, ip, ip, ip]
@@ -131,7 +132,7 @@ def _points_array(points):
 
 def nova_make_transforms(points, m, r=3, row_scaling=None, matrix_dtype="f32"):
     """points: finite interpolation points as ints, Fractions or (num, den) pairs.
-    row_scaling: None, "balanced" or (log2_b, log2_g); matrix_dtype: "f32" or "f16"
+    row_scaling: None, "balanced" or (log2_b, log2_g); matrix_dtype: "f32", "f16" or "int8"
     (nova_make_transforms_ex)."""
     arr = _points_array(points)
     handle = ctypes.c_void_p()
@@ -150,7 +151,7 @@ def nova_make_transforms(points, m, r=3, row_scaling=None, matrix_dtype="f32"):
                 raise ValueError("row_scaling needs one exponent per matrix row")
             mode = NOVA_ROWS_GIVEN
             b_arr, g_arr = (ctypes.c_int * n)(*log2_b), (ctypes.c_int * n)(*log2_g)
-        md = {"f32": NOVA_MATRIX_F32, "f16": NOVA_MATRIX_F16}[matrix_dtype]
+        md = {"f32": NOVA_MATRIX_F32, "f16": NOVA_MATRIX_F16, "int8": NOVA_MATRIX_INT8}[matrix_dtype]
         _check(lib().nova_make_transforms_ex(arr, len(points), m, r, mode, b_arr, g_arr, md, ctypes.byref(handle)),
                "nova_make_transforms_ex")
     mm, rr, nn, sym = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
@@ -163,6 +164,15 @@ def nova_get_row_scaling(t):
     b, g = (ctypes.c_int * t.n)(), (ctypes.c_int * t.n)()
     _check(lib().nova_get_row_scaling(t.handle, b, g), "nova_get_row_scaling")
     return list(b), list(g)
+
+
+def nova_get_matrix_int8(t, which):
+    """(codes as nested lists, scale) of one matrix of a handle made with matrix_dtype='int8'."""
+    rows, cols = _matrix_shape(t, which)
+    buf = (ctypes.c_int8 * (rows * cols))()
+    scale = ctypes.c_double()
+    _check(lib().nova_get_matrix_int8(t.handle, which, buf, ctypes.byref(scale)), "nova_get_matrix_int8")
+    return [[buf[i * cols + j] for j in range(cols)] for i in range(rows)], scale.value
 
 
 def _matrix_shape(t, which):

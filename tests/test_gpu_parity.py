@@ -299,6 +299,38 @@ def test_row_scaling_and_fp16_matrices_follow_the_emulation():
         assert rel_l2(got["y"], y_o) < 5e-3
 
 
+def test_int8_matrices_follow_the_emulation_and_the_printed_ordering():
+    # A, B^T, G quantised to INT8 per tensor (Sec. "INT8 Convolution Error Validation"), inputs and
+    # kernels uniform in [-1, 1] as there, binary32 storage so that the matrix quantisation is the
+    # only coarse rounding: the layer error against the fp64 definition must sit where the printed
+    # tile errors sit (standard F(4,3) 7.1e-2, discovered 2.1e-2 / 1.2e-1 / 5.9e-1)
+    rng = np.random.default_rng(44)
+    x = rng.uniform(-1.0, 1.0, (2, 16, 20, 27)).astype(np.float32)
+    w = rng.uniform(-1.0, 1.0, (12, 16, 3, 3)).astype(np.float32)
+    x64, w64 = x.astype(np.float64), w.astype(np.float64)
+    want = conv.direct_conv2d(x64, w64)
+    errs = {}
+    for name, m in (("standard", 4), ("nova", 4), ("nova", 6), ("nova", 8)):
+        say(f"[case] INT8 matrices, {name} F({m},3)")
+        points = synth.point_set(name, m)
+        t = nova.nova_make_transforms(points, m, 3, matrix_dtype="int8")
+        got = run_stages(t, x, w)
+        y_o, U_o, V_o, _ = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=32, transform_dtype="int8",
+                                                        want_intermediates=True)
+        same(got["U"], U_o, "U")
+        same(got["V"], V_o, "V")
+        errs[(name, m)] = rel_l2(got["y"], want)
+        gap = rel_l2(got["y"], y_o)
+        say(f"  rel-L2 vs fp64 definition {errs[(name, m)]:.3e}; vs emulation {gap:.3e}")
+        # binary32 accumulation order (device) against fp64 accumulation (emulation): three orders of
+        # magnitude below the effect of the quantised matrices
+        assert gap < 1e-3 * errs[(name, m)]
+    assert 0.5 * 7.1e-2 < errs[("standard", 4)] < 2 * 7.1e-2
+    assert 0.5 * 2.1e-2 < errs[("nova", 4)] < 2 * 2.1e-2
+    assert 0.5 * 1.24e-1 < errs[("nova", 6)] < 2 * 1.24e-1
+    assert 0.5 * 5.92e-1 < errs[("nova", 8)] < 2 * 5.92e-1
+
+
 def test_slabs_and_workspace_errors():
     say("[case] slab loop and workspace checks")
     points = synth.point_set("nova", 4)

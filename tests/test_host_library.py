@@ -75,6 +75,24 @@ def test_row_scaling_and_fp16_matrices_equal_oracle(name, m):
         assert nova.nova_get_matrix(t16, which) == mat           # the exact matrices are untouched
 
 
+@pytest.mark.parametrize("name,m", ALL_SETS)
+def test_int8_matrices_equal_oracle(name, m):
+    points = synth.point_set(name, m)
+    exact_mats = ct.cook_toom([Fr(a, b) for a, b in points], m, 3)
+    t = nova.nova_make_transforms(points, m, 3, matrix_dtype="int8")
+    assert t.symmetric
+    for which, mat in zip((nova.NOVA_MATRIX_A, nova.NOVA_MATRIX_BT, nova.NOVA_MATRIX_G), exact_mats):
+        vals, codes, s = ct.quantize_int8(mat)
+        got_codes, got_scale = nova.nova_get_matrix_int8(t, which)
+        assert got_codes == codes
+        assert got_scale == s.numerator / s.denominator
+        assert np.array_equal(np.array(nova.nova_get_matrix_f32(t, which), dtype=np.float32), ct.to_f32(vals))
+        assert np.array_equal(np.array(nova.nova_get_matrix_f64(t, which)), ct.to_f64(vals))
+        assert nova.nova_get_matrix(t, which) == mat
+    with pytest.raises(nova.NovaError):
+        nova.nova_get_matrix_int8(nova.nova_make_transforms(points, m, 3), nova.NOVA_MATRIX_A)
+
+
 def test_fp16_matrix_rounding_covers_subnormals():
     # G entries of wide integer point sets fall below 2^-14: 1/F_p = 1/40320 for F(8,3)
     pts = synth.point_set("standard", 8)
