@@ -144,6 +144,28 @@ def main():
                     frac=round(dom["gbs"] / HBM_PEAK_GBS, 4), traffic=traffic,
                     launch_us=round(dom["us"], 2), algorithmic_bytes=dom["bytes"])
 
+    # ---- the same step with the products M kept in binary16 (half the M traffic, one more rounding):
+    # reported beside the headline, never as `value`
+    variant = None
+    if dt == nova.NOVA_F16 and not args.m_f16:
+        vflags = flags | nova.NOVA_FLAG_M_F16
+        ws2 = torch.empty(nova.nova_conv2d_workspace_bytes(N, C, H, W, K, m, dt, vflags, args.images_per_slab),
+                          dtype=torch.uint8, device=dev)
+        y2 = torch.empty_like(y)
+        for _ in range(args.warmup):
+            nova.nova_winograd_conv2d(t, xd, U, K, y=y2, flags=vflags, workspace=ws2)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            nova.nova_winograd_conv2d(t, xd, U, K, y=y2, flags=vflags, workspace=ws2)
+        e1.record()
+        torch.cuda.synchronize()
+        v_ms = e0.elapsed_time(e1) / args.steps
+        variant = dict(flags="NOVA_FLAG_M_F16", ms_per_step=round(v_ms, 4),
+                       value=round(direct_flop / (v_ms * 1e-3) / 1e12, 2), unit="TFLOP/s")
+        del ws2
+
     if args.copy_calibration:
         src = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -172,6 +194,10 @@ def main():
         got = y[:n_cpu].cpu().numpy().astype(np.float64)
         fin = np.isfinite(got)
         result_extra["nonfinite_frac"] = float(1.0 - fin.mean())
+        if variant is not None:
+            got2 = y2[:n_cpu].cpu().numpy().astype(np.float64)
+            if np.isfinite(got2).all():
+                variant["rel_l2_vs_fp64"] = float(np.linalg.norm(got2 - ref) / np.linalg.norm(ref))
         if fin.all():
             result_extra["rel_l2_vs_fp64"] = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
             emu = oracle_conv.winograd_conv2d_emulated(x[:2].astype(np.float64), w64,
@@ -194,6 +220,8 @@ def main():
         "stages": {k: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()}
                    for k, v in stages.items()},
     }
+    if variant is not None:
+        out["variant_products_f16"] = variant
     out.update(result_extra)
     print(json.dumps(out))
 

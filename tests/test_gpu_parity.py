@@ -10,6 +10,7 @@ Bars
                          fp64 definition (the GPU adds fp32 accumulation and an fp32 output
                          transform on top of what the emulation rounds)
 """
+import os
 import sys
 from fractions import Fraction as Fr
 
@@ -23,6 +24,9 @@ from paper_2512_18453_amd import nova, synth
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
+
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def say(msg):
@@ -329,6 +333,48 @@ def test_int8_matrices_follow_the_emulation_and_the_printed_ordering():
     assert 0.5 * 2.1e-2 < errs[("nova", 4)] < 2 * 2.1e-2
     assert 0.5 * 1.24e-1 < errs[("nova", 6)] < 2 * 1.24e-1
     assert 0.5 * 5.92e-1 < errs[("nova", 8)] < 2 * 5.92e-1
+
+
+def test_fp16_error_per_tile_size_and_point_set():
+    # the accuracy half of the metric: relative L2 error of the fp16 device path against the fp64
+    # definition, per tile size and point set, on the mid-size layer shape (N=8, C=K=64, 56x56,
+    # half-normal inputs, He-normal weights).  Orderings the paper reports: discovered points beat
+    # integer points from F(4,3) on; integer-point F(8,3) leaves the binary16 range; discovered
+    # F(8,3) stays finite.  The table is also written to gpurun_out/ for the record.
+    cfg = synth.LAYER_CONFIGS["mid_f63_fp16"]
+    x, w = synth.make_layer(cfg["N"], cfg["C"], cfg["K"], cfg["H"], cfg["W"], seed=cfg["seed"], dtype="f16",
+                            x_dist=cfg["x_dist"])
+    xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+    want = conv.direct_conv2d(x.astype(np.float64), w.astype(np.float64))
+    rows, err = [], {}
+    for m, name, kw in [(2, "standard", {}), (4, "standard", {}), (4, "nova", {}), (4, "dyadic", {}),
+                        (6, "standard", {}), (6, "classic_half", {}), (6, "nova", {}),
+                        (8, "standard", {}), (8, "standard", {"row_scaling": "balanced"}), (8, "nova", {}),
+                        (8, "nova", {"row_scaling": "balanced"})]:
+        t = nova.nova_make_transforms(synth.point_set(name, m), m, 3, **kw)
+        for flags, label in ((0, "fp32 M"), (nova.NOVA_FLAG_M_F16, "fp16 M")):
+            y = nova.nova_winograd_conv2d(t, xd, nova.nova_filter_transform(t, wd), cfg["K"], flags=flags)
+            y = y.cpu().numpy().astype(np.float64)
+            bad = float((~np.isfinite(y)).mean())
+            e = rel_l2(y, want) if bad == 0 else float("nan")
+            key = (m, name + ("+balanced" if kw else ""), label)
+            err[key] = (e, bad)
+            rows.append(f"F({m},3) {key[1]:22s} {label}  rel-L2 {e:10.3e}  non-finite {bad:6.3f}")
+            say("  " + rows[-1])
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    with open(os.path.join(ROOT, "gpurun_out", "fp16_error_table.txt"), "w") as fh:
+        fh.write("\n".join(rows) + "\n")
+    e = lambda m, name: err[(m, name, "fp32 M")][0]
+    # F(4,3): all point sets are fine in fp16 (a few 1e-3); F(6,3): the integer points {0,+-1,+-2,+-3}
+    # lose more than an order of magnitude against the discovered ones.  (The classic set with +-1/2
+    # is *not* worse than the discovered set on this data -- reported, not asserted either way.)
+    assert max(e(4, "nova"), e(4, "standard"), e(4, "dyadic")) < 5e-3
+    assert e(6, "nova") < 0.1 * e(6, "standard") and e(6, "classic_half") < e(6, "standard")
+    assert err[(8, "standard", "fp32 M")][1] > 0.9                  # blow-up
+    assert err[(8, "nova", "fp32 M")][1] == 0 and e(8, "nova") < 1.0          # recovery
+    assert err[(8, "standard+balanced", "fp32 M")][1] < 0.01        # range fixed, conditioning not
+    assert abs(e(8, "nova+balanced") - e(8, "nova")) < 0.05 * e(8, "nova")
+    assert e(2, "standard") < e(4, "standard") < e(6, "standard")
 
 
 def test_slabs_and_workspace_errors():
