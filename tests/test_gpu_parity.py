@@ -493,3 +493,54 @@ def test_vgg_stack_reduced_size(m):
             act = pooled
         else:
             act = y
+
+
+def test_resnet_shapes_full_batch_sampled_images():
+    # the same four shapes at the full batch of 256; the oracle evaluates three sampled images
+    points = synth.point_set("nova", 8)
+    t = nova.nova_make_transforms(points, 8, 3)
+    sample = [0, 101, 255]
+    for idx, (ch, hw) in enumerate(synth.RESNET_SHAPES):
+        say(f"[case] ResNet-style shape C=K={ch} H=W={hw}, batch 256, images {sample}")
+        x, w = synth.make_layer(256, ch, ch, hw, hw, seed=5100 + idx, dtype="f16")
+        xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+        U = nova.nova_filter_transform(t, wd)
+        y = nova.nova_winograd_conv2d(t, xd, U, ch)
+        torch.cuda.synchronize()
+        got = y[sample].cpu().numpy().astype(np.float64)
+        y_o = conv.winograd_conv2d_emulated(x[sample].astype(np.float64), w.astype(np.float64), pts(points), 8,
+                                            storage=16)
+        err = rel_l2(got, y_o)
+        say(f"  rel-L2 vs emulation {err:.3e}")
+        assert np.isfinite(got).all() and err < 5e-3
+        del xd, y
+
+
+@pytest.mark.parametrize("m", [6, 8])
+def test_vgg_stack_full_size_sampled_images(m):
+    # the 13-layer stack at its full size (32 x 3 x 224 x 224; the library's default slabs), each
+    # layer checked on two sampled images against the emulation fed with the GPU's input to that layer
+    points = synth.point_set("nova", m)
+    t = nova.nova_make_transforms(points, m, 3)
+    rng = np.random.default_rng(4100 + m)
+    sample = [0, 31]
+    act = torch.from_numpy(rng.standard_normal((32, 3, 224, 224)).astype(np.float16)).to(DEV)
+    for layer, (cin, cout) in enumerate(synth.VGG16_LAYERS, start=1):
+        w = (rng.standard_normal((cout, cin, 3, 3)) * np.sqrt(2.0 / (9.0 * cin))).astype(np.float16)
+        say(f"[case] full VGG stack F({m},3) layer {layer}: {cin}->{cout} @ {act.shape[2]}x{act.shape[3]}")
+        U = nova.nova_filter_transform(t, torch.from_numpy(w).to(DEV))
+        y = nova.nova_winograd_conv2d(t, act, U, cout, flags=nova.NOVA_FLAG_RELU)
+        torch.cuda.synchronize()
+        x64 = act[sample].cpu().numpy().astype(np.float64)
+        y_o = conv.winograd_conv2d_emulated(x64, w.astype(np.float64), pts(points), m, storage=16, relu=True)
+        got = y[sample].cpu().numpy().astype(np.float64)
+        err = rel_l2(got, y_o)
+        say(f"  rel-L2 vs emulation {err:.3e}")
+        assert np.isfinite(got).all() and err < 5e-3
+        if layer in synth.VGG16_POOL_AFTER:
+            pooled = nova.nova_relu_maxpool2x2(y)
+            assert np.array_equal(pooled[sample].cpu().numpy().astype(np.float64), conv.relu_maxpool2x2(got))
+            act = pooled
+        else:
+            act = y
+        del y
