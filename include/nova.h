@@ -120,6 +120,27 @@ int nova_get_row_scaling(const nova_transforms *t, int *log2_b, int *log2_g);
 int nova_get_matrix_int8(const nova_transforms *t, int which, int8_t *codes, double *scale);
 void nova_free_transforms(nova_transforms *t);
 
+/*
+ * Point discovery, the deterministic steps (host only).
+ *
+ * nova_symmetric_search: exhaustive search over symmetric configurations {0, +-p1, +-p2, ..}
+ * (Sec. "Symmetric Search", Alg. "Symmetric Search"): n - 1 = m + r - 2 finite points, zero plus
+ * (n - 2) / 2 pairs when n - 1 is odd, (n - 1) / 2 pairs when it is even; the magnitudes are all
+ * a/b with 1 <= b <= d_max and 1 <= a <= 5b; the configuration with the lowest spectral condition
+ * number of its Vandermonde matrix wins (first in lexicographic order of ascending magnitudes
+ * among equals) and is verified exactly before it is returned.  With d_max = 6 this yields the
+ * discovered point sets the paper prints for F(4,3), F(6,3) and F(8,3).
+ * points_out: n - 1 entries, in the order 0, +p1, -p1, +p2, -p2, .. (ready for
+ * nova_make_transforms); *kappa_out: its condition number.  1 <= d_max <= 64; NOVA_EUNSUPPORTED
+ * if more than 2e8 combinations would have to be tried.  Uses up to 16 host threads.
+ *
+ * nova_snap_to_rational: the fraction a/b nearest to x with 1 <= b <= d_max, |a| <= 5b
+ * (Sec. "Snap-to-Rational"); among equally near ones the first in the order b ascending, then a
+ * ascending.  Exact comparison; *out is reduced.  1 <= d_max <= 1000, x finite.
+ */
+int nova_symmetric_search(int m, int r, int d_max, nova_rational *points_out, double *kappa_out);
+int nova_snap_to_rational(double x, int d_max, nova_rational *out);
+
 /* m, r, n of a handle; `symmetric` = 1 when the points come as 0, +a1, -a1, +a2, -a2, ...
  * (the order for which the device transforms share work between +a and -a). Any pointer may be NULL. */
 int nova_transforms_shape(const nova_transforms *t, int *m, int *r, int *n, int *symmetric);

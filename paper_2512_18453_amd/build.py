@@ -17,7 +17,7 @@ SRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnova.so")
 
-SOURCES = ["transforms.cpp", "api.cpp", "filter_transform.hip", "input_transform.hip",
+SOURCES = ["transforms.cpp", "discovery.cpp", "api.cpp", "filter_transform.hip", "input_transform.hip",
            "contract.hip", "output_transform.hip", "pool.hip"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-Wno-unused-function"]
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -93,6 +93,8 @@ struct nova_transforms {
 // ---- kernel launchers (defined in the .hip files); all return a hipError_t as int ----
 namespace nova {
 void set_last_hip_error(int err);
+// sigma_max / sigma_min of a row-major matrix (one-sided Jacobi)
+double spectral_condition(const std::vector<double> &mat, int rows, int cols);
 int device_cu_count();          // compute units of the current device (256 if the query fails)
 
 int launch_filter_transform(const nova_transforms *t, const void *w, int K, int C, int dtype,

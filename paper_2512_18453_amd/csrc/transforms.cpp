@@ -144,6 +144,10 @@ Rat times_pow2(RatCtx &cx, const Rat &v, int e)
 
 }  // namespace
 
+namespace nova {
+double spectral_condition(const std::vector<double> &mat, int rows, int cols) { return kappa2(mat, rows, cols); }
+}
+
 extern "C" int nova_make_transforms(const nova_rational *finite_points, int n_points, int m, int r,
                                     nova_transforms **out)
 {

@@ -21,7 +21,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnova.so
 _lib = None
 
 EXPORTS = [
-    "nova_make_transforms", "nova_make_transforms_ex", "nova_get_row_scaling", "nova_get_matrix_int8", "nova_free_transforms", "nova_transforms_shape", "nova_get_matrix",
+    "nova_make_transforms", "nova_make_transforms_ex", "nova_get_row_scaling", "nova_get_matrix_int8", "nova_free_transforms", "nova_symmetric_search", "nova_snap_to_rational", "nova_transforms_shape", "nova_get_matrix",
     "nova_get_matrix_f64", "nova_get_matrix_f32", "nova_kappa", "nova_filter_bytes", "nova_input_bytes",
     "nova_product_bytes", "nova_filter_transform", "nova_conv2d_workspace_bytes", "nova_winograd_conv2d",
     "nova_input_transform", "nova_contract", "nova_output_transform", "nova_relu_maxpool2x2",
@@ -56,6 +56,8 @@ def lib():
         L.nova_get_row_scaling.argtypes = [vp, ip, ip]
         L.nova_get_matrix_int8.argtypes = [vp, i, ctypes.POINTER(ctypes.c_int8), ctypes.POINTER(ctypes.c_double)]
         L.nova_free_transforms.argtypes = [vp]
+        L.nova_symmetric_search.argtypes = [i, i, i, ctypes.POINTER(nova_rational), ctypes.POINTER(ctypes.c_double)]
+        L.nova_snap_to_rational.argtypes = [ctypes.c_double, i, ctypes.POINTER(nova_rational)]
         L.nova_free_transforms.restype = None
         L.nova_transforms_shape.argtypes = [vp, ip, ip, ip, ip]
         L.nova_get_matrix.argtypes = [vp, i, ctypes.POINTER(nova_rational)]
@@ -157,6 +159,21 @@ def nova_make_transforms(points, m, r=3, row_scaling=None, matrix_dtype="f32"):
     mm, rr, nn, sym = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
     _check(lib().nova_transforms_shape(handle, mm, rr, nn, sym), "nova_transforms_shape")
     return Transforms(handle, mm.value, rr.value, nn.value, bool(sym.value))
+
+
+def nova_symmetric_search(m, r=3, d_max=6):
+    """(points, kappa): best symmetric configuration as Fractions in canonical order."""
+    count = m + r - 2
+    buf = (nova_rational * max(count, 1))()
+    kappa = ctypes.c_double()
+    _check(lib().nova_symmetric_search(m, r, d_max, buf, ctypes.byref(kappa)), "nova_symmetric_search")
+    return [Fraction(buf[idx].num, buf[idx].den) for idx in range(count)], kappa.value
+
+
+def nova_snap_to_rational(x, d_max=10):
+    out = nova_rational()
+    _check(lib().nova_snap_to_rational(float(x), d_max, ctypes.byref(out)), "nova_snap_to_rational")
+    return Fraction(out.num, out.den)
 
 
 def nova_get_row_scaling(t):

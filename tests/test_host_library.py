@@ -10,6 +10,7 @@ import numpy as np
 import pytest
 
 from oracle import cook_toom as ct
+from oracle import discovery
 from paper_2512_18453_amd import nova, synth
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -187,3 +188,40 @@ def test_sizes_follow_documented_layouts():
     assert one == 100 * 8 * 49 * 32 * 2 + 100 * 8 * 128 * 32 * 4
     default = nova.nova_conv2d_workspace_bytes(32, 256, 56, 56, 256, 8, nova.NOVA_F16, 0, 0)
     assert default == whole
+
+
+@pytest.mark.parametrize("m,r,d_max", [(2, 3, 3), (2, 3, 10), (3, 3, 4), (4, 3, 6), (4, 3, 10), (5, 3, 5), (6, 3, 6),
+                                       (8, 3, 6), (2, 5, 6), (4, 5, 5)])
+def test_symmetric_search_equals_oracle(m, r, d_max):
+    points, kappa = nova.nova_symmetric_search(m, r, d_max)
+    want_points, want_kappa = discovery.symmetric_search(m, r, d_max)
+    assert points == want_points
+    assert kappa == pytest.approx(want_kappa, rel=1e-9)
+    # the result is ready for the constructor, and is the paired order the device kernels exploit
+    t = nova.nova_make_transforms(points, m, r)
+    assert t.symmetric == ((m + r) % 2 == 1)           # zero is part of the set only for an odd number of points
+
+
+def test_symmetric_search_rejects_bad_arguments():
+    L = nova.lib()
+    buf, kappa = (nova.nova_rational * 16)(), ctypes.c_double()
+    assert L.nova_symmetric_search(0, 3, 6, buf, ctypes.byref(kappa)) == -1
+    assert L.nova_symmetric_search(4, 3, 0, buf, ctypes.byref(kappa)) == -1
+    assert L.nova_symmetric_search(4, 3, 65, buf, ctypes.byref(kappa)) == -1
+    assert L.nova_symmetric_search(4, 3, 6, None, ctypes.byref(kappa)) == -1
+    assert L.nova_symmetric_search(14, 3, 6, buf, ctypes.byref(kappa)) == -6      # too many combinations
+    assert L.nova_symmetric_search(1, 1, 6, buf, ctypes.byref(kappa)) == -1       # fewer than two finite points
+
+
+def test_snap_to_rational_equals_oracle():
+    rng = np.random.default_rng(12)
+    xs = list(rng.uniform(-6.5, 6.5, 300)) + [0.0, 0.5, -0.5, 1e-13, -1e-300, 5.0, 5.5, -5.999, 6.0, 123.0, 0.8333, 1 / 3,
+                                               2 / 7, 0.1 + 0.2, 1.25, -4.95]
+    for d_max in (1, 2, 6, 10, 37):
+        for x in xs:
+            assert nova.nova_snap_to_rational(x, d_max) == discovery.snap_to_rational(x, d_max), (x, d_max)
+    L = nova.lib()
+    out = nova.nova_rational()
+    assert L.nova_snap_to_rational(float("nan"), 10, ctypes.byref(out)) == -1
+    assert L.nova_snap_to_rational(0.5, 0, ctypes.byref(out)) == -1
+    assert L.nova_snap_to_rational(0.5, 10, None) == -1
