@@ -37,12 +37,12 @@ def _load():
         lib.nova_oracle_threads.restype = i
         lib.nova_oracle_round_f16.argtypes = [dp, dp, ctypes.c_long]
         lib.nova_oracle_round_f16.restype = None
-        lib.nova_oracle_direct_conv2d.argtypes = [dp, dp, dp, i, i, i, i, i]
+        lib.nova_oracle_direct_conv2d.argtypes = [dp, dp, dp, i, i, i, i, i, i]
         lib.nova_oracle_direct_conv2d.restype = i
-        lib.nova_oracle_winograd_conv2d_f64.argtypes = [dp, dp, dp, i, i, i, i, i, i, dp, dp, dp]
+        lib.nova_oracle_winograd_conv2d_f64.argtypes = [dp, dp, dp, i, i, i, i, i, i, i, dp, dp, dp]
         lib.nova_oracle_winograd_conv2d_f64.restype = i
         lib.nova_oracle_winograd_conv2d_emulated.argtypes = (
-            [dp, dp, dp, i, i, i, i, i, i, fp, fp, dp, i, i, i, i, dp, dp, dp])
+            [dp, dp, dp, i, i, i, i, i, i, i, fp, fp, dp, i, i, i, i, dp, dp, dp])
         lib.nova_oracle_winograd_conv2d_emulated.restype = i
         _lib = lib
     return _lib
@@ -74,29 +74,29 @@ def round_f16(values):
 
 
 def direct_conv2d(x, g):
-    """fp64 3x3 convolution, stride 1, pad 1, no flip, no bias (Sec. 2.1 definition).
-    x [N,C,H,W], g [K,C,3,3] -> y [N,K,H,W] fp64."""
+    """fp64 r x r convolution (r odd), stride 1, pad (r-1)/2, no flip, no bias (Sec. 2.1
+    definition; 3 x 3 is the paper's case).  x [N,C,H,W], g [K,C,r,r] -> y [N,K,H,W] fp64."""
     x, g = _c64(x), _c64(g)
     N, C, H, W = x.shape
-    K = g.shape[0]
-    assert g.shape == (K, C, 3, 3)
+    K, r = g.shape[0], g.shape[-1]
+    assert g.shape == (K, C, r, r) and r % 2 == 1
     y = np.empty((N, K, H, W), dtype=np.float64)
-    rc = _load().nova_oracle_direct_conv2d(_d(x), _d(g), _d(y), N, C, H, W, K)
+    rc = _load().nova_oracle_direct_conv2d(_d(x), _d(g), _d(y), N, C, H, W, K, r)
     if rc:
         raise RuntimeError(f"oracle direct conv failed ({rc})")
     return y
 
 
 def winograd_conv2d_f64(x, g, points, m):
-    """fp64 Winograd F(m x m, 3 x 3) with the matrices of cook_toom(points, m) rounded once
-    to fp64."""
-    A, BT, G = ct.cook_toom(points, m, 3)
+    """fp64 Winograd F(m x m, r x r), r = g.shape[-1], with the matrices of
+    cook_toom(points, m, r) rounded once to fp64."""
     x, g = _c64(x), _c64(g)
     N, C, H, W = x.shape
-    K = g.shape[0]
+    K, r = g.shape[0], g.shape[-1]
+    A, BT, G = ct.cook_toom(points, m, r)
     y = np.empty((N, K, H, W), dtype=np.float64)
     A64, BT64, G64 = ct.to_f64(A), ct.to_f64(BT), ct.to_f64(G)
-    rc = _load().nova_oracle_winograd_conv2d_f64(_d(x), _d(g), _d(y), N, C, H, W, K, m,
+    rc = _load().nova_oracle_winograd_conv2d_f64(_d(x), _d(g), _d(y), N, C, H, W, K, m, r,
                                                  _d(A64), _d(BT64), _d(G64))
     if rc:
         raise RuntimeError(f"oracle winograd conv failed ({rc})")
@@ -125,8 +125,8 @@ def int8_matrix_tile_error(points, m, trials=100, seed=0):
     return total / trials
 
 
-def _matrices(points, m, row_scaling):
-    A, BT, G = ct.cook_toom(points, m, 3)
+def _matrices(points, m, row_scaling, r=3):
+    A, BT, G = ct.cook_toom(points, m, r)
     if row_scaling is None:
         return A, BT, G
     if isinstance(row_scaling, str):
@@ -150,7 +150,8 @@ def winograd_conv2d_emulated(x, g, points, m, storage=16, m_storage=32, v_exact=
     row_scaling: None, "balanced", or (log2_b, log2_g) -- power-of-two row scales applied to
     the exact matrices before any rounding (cook_toom.scale_rows).
     Returns y, or (y, U, V, M) with U [n*n,K,C], V [n*n,T,C], M [n*n,T,K] as fp64."""
-    A, BT, G = _matrices(points, m, row_scaling)
+    r = np.shape(g)[-1]
+    A, BT, G = _matrices(points, m, row_scaling, r)
     if transform_dtype == "f32":
         A32, BT32, G64 = ct.to_f32(A), ct.to_f32(BT), ct.to_f64(G)
     elif transform_dtype == "f16":
@@ -166,7 +167,7 @@ def winograd_conv2d_emulated(x, g, points, m, storage=16, m_storage=32, v_exact=
     x, g = _c64(x), _c64(g)
     N, C, H, W = x.shape
     K = g.shape[0]
-    n = m + 2
+    n = m + r - 1
     T = N * (-(-H // m)) * (-(-W // m))
     y = np.empty((N, K, H, W), dtype=np.float64)
     null = ctypes.POINTER(ctypes.c_double)()
@@ -177,7 +178,7 @@ def winograd_conv2d_emulated(x, g, points, m, storage=16, m_storage=32, v_exact=
         M = np.empty((n * n, T, K), dtype=np.float64)
     A32, BT32 = np.ascontiguousarray(A32), np.ascontiguousarray(BT32)
     rc = _load().nova_oracle_winograd_conv2d_emulated(
-        _d(x), _d(g), _d(y), N, C, H, W, K, m, _f(A32), _f(BT32), _d(G64),
+        _d(x), _d(g), _d(y), N, C, H, W, K, m, r, _f(A32), _f(BT32), _d(G64),
         storage, m_storage, int(bool(v_exact)), int(bool(relu)),
         _d(U) if want_intermediates else null,
         _d(V) if want_intermediates else null,

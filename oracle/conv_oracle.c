@@ -1,11 +1,12 @@
 /*
- * CPU oracle for 3x3, stride-1, pad-1 convolution and its Winograd F(m x m, 3 x 3)
+ * CPU oracle for r x r (r odd; 3 x 3 in the paper's experiments), stride-1, pad-(r-1)/2 convolution
+ * and its Winograd F(m x m, r x r)
  * evaluation.  TEST INFRASTRUCTURE ONLY: plain, slow, written to be checked by eye.
  * It shares no code with the HIP library.
  *
  *   direct     the definition  y_i = sum_k g_k x_{i+k}  of Sec. 2.1 applied along both
  *              image axes and summed over input channels (no kernel flip, no bias).
- *   winograd   Y = A^T [ (G g G^T) * (B^T d B) ] A per n x n tile, n = m + 2
+ *   winograd   Y = A^T [ (G g G^T) * (B^T d B) ] A per n x n tile, n = m + r - 1
  *              (Sec. 2.1 steps 1-4 nested in 2D, App. "2D Extension via Kronecker
  *              Products"), channel sum taken in the transformed domain.
  *   emulated   the same with the intermediate tensors rounded to a storage format
@@ -15,7 +16,7 @@
  *
  * All tensors cross this interface as fp64 arrays (values that are already exactly
  * representable in the storage format when a storage format is emulated).
- * Layouts: x [N][C][H][W], g [K][C][3][3], y [N][K][H][W], matrices row-major with one
+ * Layouts: x [N][C][H][W], g [K][C][r][r], y [N][K][H][W], matrices row-major with one
  * row per interpolation point (last row = the point at infinity).
  * Winograd-domain tensors: U [n*n][K][C], V [n*n][T][C], M [n*n][T][K] with
  * xi = i*n + j and t = (image*tiles_h + tile_row)*tiles_w + tile_col.
@@ -27,7 +28,7 @@
 #include <omp.h>
 #endif
 
-#define MAXN 16 /* largest n = m + 2 handled (m <= 14) */
+#define MAXN 16 /* largest n = m + r - 1 handled */
 
 int nova_oracle_threads(void)
 {
@@ -74,9 +75,10 @@ void nova_oracle_round_f16(const double *in, double *out, long count)
 /* ---------------------------------------------------------------- direct convolution */
 
 int nova_oracle_direct_conv2d(const double *x, const double *g, double *y,
-                              int N, int C, int H, int W, int K)
+                              int N, int C, int H, int W, int K, int r)
 {
-    if (!x || !g || !y || N < 0 || C < 1 || H < 1 || W < 1 || K < 1) return -1;
+    if (!x || !g || !y || N < 0 || C < 1 || H < 1 || W < 1 || K < 1 || r < 1 || r % 2 == 0) return -1;
+    const int pad = (r - 1) / 2;
 #pragma omp parallel for collapse(2) schedule(static)
     for (int n = 0; n < N; ++n)
         for (int k = 0; k < K; ++k) {
@@ -84,17 +86,18 @@ int nova_oracle_direct_conv2d(const double *x, const double *g, double *y,
             for (size_t i = 0; i < (size_t)H * W; ++i) yp[i] = 0.0;
             for (int c = 0; c < C; ++c) {
                 const double *xp = x + ((size_t)n * C + c) * H * W;
-                const double *gp = g + ((size_t)k * C + c) * 9;
-                for (int a = 0; a < 3; ++a)
-                    for (int b = 0; b < 3; ++b) {
-                        double gv = gp[a * 3 + b];
+                const double *gp = g + ((size_t)k * C + c) * r * r;
+                for (int a = 0; a < r; ++a)
+                    for (int b = 0; b < r; ++b) {
+                        double gv = gp[a * r + b];
                         for (int h = 0; h < H; ++h) {
-                            int hh = h + a - 1;
+                            int hh = h + a - pad;
                             if (hh < 0 || hh >= H) continue;
-                            int w_lo = b == 0 ? 1 : 0;            /* keep w + b - 1 inside [0, W) */
-                            int w_hi = b == 2 ? W - 1 : W;
-                            for (int w = w_lo; w < w_hi; ++w)
-                                yp[(size_t)h * W + w] += gv * xp[(size_t)hh * W + (w + b - 1)];
+                            for (int w = 0; w < W; ++w) {
+                                int ww = w + b - pad;
+                                if (ww < 0 || ww >= W) continue;          /* zero border */
+                                yp[(size_t)h * W + w] += gv * xp[(size_t)hh * W + ww];
+                            }
                         }
                     }
             }
@@ -124,21 +127,21 @@ static void sandwich_f64(const double *L, int rows_l, int inner,
         }
 }
 
-static void load_tile(const double *plane, int H, int W, int h0, int w0, int n, double *d)
+static void load_tile(const double *plane, int H, int W, int h0, int w0, int n, int pad, double *d)
 {
     for (int a = 0; a < n; ++a)
         for (int b = 0; b < n; ++b) {
-            int hh = h0 - 1 + a, ww = w0 - 1 + b;   /* pad 1; beyond the image reads as zero */
+            int hh = h0 - pad + a, ww = w0 - pad + b;   /* beyond the image reads as zero */
             d[a * n + b] = (hh >= 0 && hh < H && ww >= 0 && ww < W) ? plane[(size_t)hh * W + ww] : 0.0;
         }
 }
 
 int nova_oracle_winograd_conv2d_f64(const double *x, const double *g, double *y,
-                                    int N, int C, int H, int W, int K, int m,
+                                    int N, int C, int H, int W, int K, int m, int r,
                                     const double *A, const double *BT, const double *G)
 {
-    int n = m + 2;
-    if (!x || !g || !y || !A || !BT || !G || n > MAXN || m < 1) return -1;
+    int n = m + r - 1, pad = (r - 1) / 2;
+    if (!x || !g || !y || !A || !BT || !G || n > MAXN || m < 1 || r < 1 || r % 2 == 0) return -1;
     int th = (H + m - 1) / m, tw = (W + m - 1) / m;
     size_t nn = (size_t)n * n;
     double *U = malloc(sizeof(double) * nn * K * C);
@@ -149,7 +152,7 @@ int nova_oracle_winograd_conv2d_f64(const double *x, const double *g, double *y,
 #pragma omp parallel for schedule(static)
     for (int kc = 0; kc < K * C; ++kc) {
         double u[MAXN * MAXN];
-        sandwich_f64(G, n, 3, g + (size_t)kc * 9, 3, G, n, u);        /* G g G^T */
+        sandwich_f64(G, n, r, g + (size_t)kc * r * r, r, G, n, u);    /* G g G^T */
         for (size_t xi = 0; xi < nn; ++xi) U[xi * K * C + kc] = u[xi];
     }
     int fail = 0;
@@ -161,7 +164,7 @@ int nova_oracle_winograd_conv2d_f64(const double *x, const double *g, double *y,
             for (int tc = 0; tc < tw; ++tc) {
                 double d[MAXN * MAXN], v[MAXN * MAXN], Mk[MAXN * MAXN], Y[MAXN * MAXN];
                 for (int c = 0; c < C; ++c) {
-                    load_tile(x + ((size_t)img * C + c) * H * W, H, W, tr * m, tc * m, n, d);
+                    load_tile(x + ((size_t)img * C + c) * H * W, H, W, tr * m, tc * m, n, pad, d);
                     sandwich_f64(BT, n, n, d, n, BT, n, v);           /* B^T d B */
                     for (size_t xi = 0; xi < nn; ++xi) V[xi * C + c] = v[xi];
                 }
@@ -216,13 +219,13 @@ static void input_transform_1d_f32(const float *BT, int n, const float *v, int v
  * U_out, V_out, M_out: optional (may be NULL) copies of the Winograd-domain tensors.
  */
 int nova_oracle_winograd_conv2d_emulated(const double *x, const double *g, double *y,
-                                         int N, int C, int H, int W, int K, int m,
+                                         int N, int C, int H, int W, int K, int m, int r,
                                          const float *A32, const float *BT32, const double *G64,
                                          int storage, int m_storage, int v_exact, int relu,
                                          double *U_out, double *V_out, double *M_out)
 {
-    int n = m + 2;
-    if (!x || !g || !y || !A32 || !BT32 || !G64 || n > MAXN || m < 1) return -1;
+    int n = m + r - 1, pad = (r - 1) / 2;
+    if (!x || !g || !y || !A32 || !BT32 || !G64 || n > MAXN || m < 1 || r < 1 || r % 2 == 0) return -1;
     if ((storage != 16 && storage != 32) || (m_storage != 16 && m_storage != 32)) return -1;
     int th = (H + m - 1) / m, tw = (W + m - 1) / m;
     size_t nn = (size_t)n * n, T = (size_t)N * th * tw;
@@ -238,7 +241,7 @@ int nova_oracle_winograd_conv2d_emulated(const double *x, const double *g, doubl
 #pragma omp parallel for schedule(static)
     for (int kc = 0; kc < K * C; ++kc) {
         double u[MAXN * MAXN];
-        sandwich_f64(G64, n, 3, g + (size_t)kc * 9, 3, G64, n, u);
+        sandwich_f64(G64, n, r, g + (size_t)kc * r * r, r, G64, n, u);
         for (size_t xi = 0; xi < nn; ++xi) U[xi * K * C + kc] = round_storage(u[xi], storage);
     }
     if (U_out) memcpy(U_out, U, sizeof(double) * nn * K * C);
@@ -253,7 +256,7 @@ int nova_oracle_winograd_conv2d_emulated(const double *x, const double *g, doubl
                 size_t t = ((size_t)img * th + tr) * tw + tc;
                 double d[MAXN * MAXN], v[MAXN * MAXN], Mk[MAXN * MAXN], Y[MAXN * MAXN];
                 for (int c = 0; c < C; ++c) {
-                    load_tile(x + ((size_t)img * C + c) * H * W, H, W, tr * m, tc * m, n, d);
+                    load_tile(x + ((size_t)img * C + c) * H * W, H, W, tr * m, tc * m, n, pad, d);
                     if (v_exact) {
                         sandwich_f64(BT64, n, n, d, n, BT64, n, v);
                     } else {

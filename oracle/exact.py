@@ -22,10 +22,13 @@ def _transpose(a):
 
 def direct_conv2d(x, g):
     """y[n][k][h][w] = sum_{c,a,b} g[k][c][a][b] * xpad[n][c][h+a][w+b], xpad = x with a
-    one-pixel zero border: stride 1, pad 1, no kernel flip (Sec. 2.1, y_i = sum_k g_k x_{i+k}).
-    x: [N][C][H][W], g: [K][C][3][3], nested lists of ints or Fractions."""
+    zero border of (r-1)/2 pixels: stride 1, no kernel flip (Sec. 2.1, y_i = sum_k g_k x_{i+k}).
+    x: [N][C][H][W], g: [K][C][r][r] (r odd; 3 in the paper's experiments), nested lists of
+    ints or Fractions."""
     N, C, H, W = len(x), len(x[0]), len(x[0][0]), len(x[0][0][0])
     K = len(g)
+    r = len(g[0][0])
+    pad = (r - 1) // 2
     y = [[[[Fraction(0)] * W for _ in range(H)] for _ in range(K)] for _ in range(N)]
     for n in range(N):
         for k in range(K):
@@ -33,9 +36,9 @@ def direct_conv2d(x, g):
                 for w in range(W):
                     acc = Fraction(0)
                     for c in range(C):
-                        for a in range(3):
-                            for b in range(3):
-                                hh, ww = h + a - 1, w + b - 1
+                        for a in range(r):
+                            for b in range(r):
+                                hh, ww = h + a - pad, w + b - pad
                                 if 0 <= hh < H and 0 <= ww < W:
                                     acc += Fraction(g[k][c][a][b]) * Fraction(x[n][c][hh][ww])
                     y[n][k][h][w] = acc
@@ -43,13 +46,14 @@ def direct_conv2d(x, g):
 
 
 def winograd_conv2d(x, g, A, BT, G):
-    """Same result through F(m x m, 3 x 3) tiles with the exact matrices A, B^T, G.
-    The padded image is cut into n x n tiles at stride m (n = m + 2); positions outside
+    """Same result through F(m x m, r x r) tiles with the exact matrices A, B^T, G.
+    The padded image is cut into n x n tiles at stride m (n = m + r - 1); positions outside
     the image, including those of a ragged last tile row / column, read as zero and the
     outputs beyond H x W are dropped."""
     N, C, H, W = len(x), len(x[0]), len(x[0][0]), len(x[0][0][0])
     K = len(g)
     n, m = len(A), len(A[0])
+    pad = (n - m) // 2                       # (r - 1) / 2
     B = _transpose(BT)
     GT = _transpose(G)
     AT = _transpose(A)
@@ -61,8 +65,8 @@ def winograd_conv2d(x, g, A, BT, G):
             for w0 in range(0, W, m):
                 V = []
                 for c in range(C):
-                    d = [[Fraction(x[img][c][h0 - 1 + a][w0 - 1 + b])
-                          if 0 <= h0 - 1 + a < H and 0 <= w0 - 1 + b < W else Fraction(0)
+                    d = [[Fraction(x[img][c][h0 - pad + a][w0 - pad + b])
+                          if 0 <= h0 - pad + a < H and 0 <= w0 - pad + b < W else Fraction(0)
                           for b in range(n)] for a in range(n)]
                     V.append(_matmul(_matmul(BT, d), B))
                 for k in range(K):

@@ -324,6 +324,66 @@ def test_emulated_relu_and_transform_dtype_option():
     assert rel_l2(y16, want) < 2e-2 and not np.array_equal(y16, y)
 
 
+# ---------------------------------------------------------------- 5 x 5 kernels (r = 5)
+
+# finite points for n - 1 = m + 3: the integer sets the r = 5 table compares against, and the symmetric-search
+# winners with d_max = 6 (oracle/discovery.py)
+R5_POINTS = {(2, "standard"): [0, 1, -1, 2, -2], (4, "standard"): [0, 1, -1, 2, -2, 3, -3],
+             (6, "standard"): [0, 1, -1, 2, -2, 3, -3, 4, -4],
+             (4, "searched"): [0, Fr(3, 5), Fr(-3, 5), 1, -1, Fr(7, 6), Fr(-7, 6)]}
+
+
+@pytest.mark.parametrize("m,name", [(2, "standard"), (4, "standard"), (4, "searched")])
+def test_r5_winograd_equals_direct_in_rational_arithmetic(m, name):
+    rnd = random.Random(500 + m)
+    A, BT, G = ct.cook_toom(R5_POINTS[(m, name)], m, 5)
+    assert (len(A), len(A[0]), len(BT[0]), len(G[0])) == (m + 4, m, m + 4, 5)
+    for (H, W) in [(m, m), (m + 3, 2 * m + 1)]:
+        x = [[[[rnd.randint(-3, 3) for _ in range(W)] for _ in range(H)] for _ in range(2)]]
+        g = [[[[rnd.randint(-3, 3) for _ in range(5)] for _ in range(5)] for _ in range(2)] for _ in range(2)]
+        assert exact.winograd_conv2d(x, g, A, BT, G) == exact.direct_conv2d(x, g)
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 4, 9, 13), (1, 2, 2, 2, 3), (1, 4, 3, 1, 1)])
+def test_r5_direct_c_vs_library_conv_and_exact(shape):
+    N, C, K, H, W = shape
+    rng = np.random.default_rng(51)
+    x = rng.standard_normal((N, C, H, W))
+    g = rng.standard_normal((K, C, 5, 5))
+    want = torch.nn.functional.conv2d(torch.from_numpy(x), torch.from_numpy(g), padding=2).numpy()
+    assert np.allclose(conv.direct_conv2d(x, g), want, rtol=0, atol=1e-12 * np.abs(want).max() * C)
+    xi = rng.integers(-3, 4, (1, 2, H, W))
+    gi = rng.integers(-3, 4, (2, 2, 5, 5))
+    assert np.array_equal(conv.direct_conv2d(xi, gi),
+                          np.array(exact.direct_conv2d(xi.tolist(), gi.tolist()), dtype=np.float64))
+
+
+@pytest.mark.parametrize("m,name,tol", [(2, "standard", 1e-13), (4, "standard", 1e-11), (4, "searched", 1e-12),
+                                        (6, "standard", 1e-8)])
+def test_r5_winograd_f64_and_emulation_vs_direct(m, name, tol):
+    rng = np.random.default_rng(60 + m)
+    points = R5_POINTS[(m, name)]
+    for (N, C, K, H, W) in [(2, 5, 3, 2 * m, 3 * m), (1, 4, 6, 2 * m + 3, m + 1)]:
+        x = rng.standard_normal((N, C, H, W))
+        g = rng.standard_normal((K, C, 5, 5))
+        want = conv.direct_conv2d(x, g)
+        assert rel_l2(conv.winograd_conv2d_f64(x, g, points, m), want) < tol
+        x32, g32 = x.astype(np.float32).astype(np.float64), g.astype(np.float32).astype(np.float64)
+        y, U, V, M = conv.winograd_conv2d_emulated(x32, g32, points, m, storage=32, want_intermediates=True)
+        n = m + 4
+        assert U.shape == (n * n, K, C) and V.shape[0] == n * n and M.shape[2] == K
+        # binary32 storage: about 2^-24 / 2^-53 = 5e8 times the fp64 figure at most; loose on purpose, this
+        # only checks that the emulation runs the r = 5 geometry end to end
+        assert rel_l2(y, conv.direct_conv2d(x32, g32)) < max(2e-6, 1e7 * tol)
+
+
+def test_r5_standard_kappa_is_the_printed_one():
+    # Table "5 x 5 kernel discovery results": standard kappa 2,075 for F(4,5) and 196.9k for F(6,5)
+    # (the same point sets as F(6,3) and F(8,3): kappa(V) depends on the points only)
+    assert ct.kappa_V(R5_POINTS[(4, "standard")]) == pytest.approx(2075, rel=5e-4)
+    assert ct.kappa_V(R5_POINTS[(6, "standard")]) == pytest.approx(196.9e3, rel=5e-4)
+
+
 def test_relu_maxpool():
     y = np.array([[[[1.0, -2.0, 3.0, 0.5], [-1.0, -3.0, 2.0, 7.0]]]])
     assert np.array_equal(conv.relu_maxpool2x2(y), np.array([[[[1.0, 7.0]]]]))
