@@ -8,8 +8,9 @@
  *
  *     Y = A^T [ (G g G^T) * (B^T d B) ] A,   summed over input channels before A^T . A,
  *
- * for each n x n input tile d (n = m + 2, tiles at stride m over the image zero-padded by
- * one pixel) and each 3 x 3 filter g; stride 1, pad 1, correlation (no kernel flip), no bias.
+ * for each n x n input tile d (n = m + r - 1, tiles at stride m over the image zero-padded by
+ * (r-1)/2 pixels) and each r x r filter g (r = 3 in the paper's experiments, r = 5 its stated
+ * extension); stride 1, correlation (no kernel flip), no bias.
  *
  * Conventions for every call
  *   - "host" pointers are ordinary process memory, "device" pointers are HIP device memory
@@ -70,7 +71,8 @@ enum {
  *                infinity row = coefficients of prod_j (t - alpha_j)
  * The result is verified against the exact identity sum_p A[p][i] B^T[p][j] G[p][k] = [j == i + k]
  * before it is returned.  Any m >= 1, r >= 1 with n <= 16 is accepted here; the device calls
- * below need r == 3 and m in {2, 4, 6, 8}.
+ * below need r == 3 with m in {2, 4, 6, 8}, or r == 5 with m in {2, 4, 6} (the 5 x 5 extension of
+ * Sec. "Extension to 5 x 5 Kernels": same n as F(4,3) .. F(8,3)).
  * *out is owned by the caller: release with nova_free_transforms.
  */
 int nova_make_transforms(const nova_rational *finite_points, int n_points, int m, int r,
@@ -169,13 +171,13 @@ int nova_kappa(const nova_transforms *t, double out[4]);
  *                                 ((xi*ceil(K/32) + k/32)*Tp + t)*32 + k%32; rows t >= T are scratch
  * U and V have the storage dtype; M is binary32 (binary16 with NOVA_FLAG_M_F16).
  */
-size_t nova_filter_bytes(int K, int C, int m, int dtype);                 /* size of U */
-size_t nova_input_bytes(int N, int C, int H, int W, int m, int dtype);    /* size of V, whole batch */
-size_t nova_product_bytes(int N, int K, int H, int W, int m, int dtype, int flags); /* size of M */
+size_t nova_filter_bytes(int K, int C, int m, int r, int dtype);                 /* size of U */
+size_t nova_input_bytes(int N, int C, int H, int W, int m, int r, int dtype);    /* size of V, whole batch */
+size_t nova_product_bytes(int N, int K, int H, int W, int m, int r, int dtype, int flags); /* size of M */
 
 /*
  * Filter transform U = G g G^T (Sec. 2.1 step 2 in 2D), evaluated in binary64 and rounded once
- * to dtype.  w: device [K][C][3][3] of dtype; U: device, nova_filter_bytes(K, C, m, dtype) bytes,
+ * to dtype.  w: device [K][C][r][r] of dtype; U: device, nova_filter_bytes(K, C, m, r, dtype) bytes,
  * fully overwritten (padding included).  Done once per weight set, off the per-call path.
  */
 int nova_filter_transform(const nova_transforms *t, const void *w, int K, int C, int dtype,
@@ -187,11 +189,12 @@ int nova_filter_transform(const nova_transforms *t, const void *w, int K, int C,
  * given.  images_per_slab = 0 asks for the library's default (as many images as fit 256 MiB of
  * V and M, at least one), N for the whole batch in one pass.  Returns 0 for invalid arguments.
  */
-size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K, int m, int dtype, int flags,
+size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K, int m, int r, int dtype, int flags,
                                    int images_per_slab);
 
 /*
- * y = conv3x3(x, w), stride 1, pad 1, through F(m x m, 3 x 3) with the handle's matrices:
+ * y = conv r x r (x, w), stride 1, zero border (r-1)/2 (3 x 3 with border 1 is the paper's case; the
+ * 5 x 5 extension takes border 2, "same" output size), through F(m x m, r x r) with the handle's matrices:
  * input transform -> n*n channel contractions -> output transform, enqueued on `stream`.
  * x: device [N][C][H][W]; U: from nova_filter_transform with the same handle, K, C, dtype;
  * y: device [N][K][H][W]; all of dtype.  H, W >= 1 arbitrary: the image is zero-extended to

@@ -16,13 +16,19 @@ static int hip_result(int err)
     return NOVA_EHIP;
 }
 
-static bool device_tile_ok(int m) { return m == 2 || m == 4 || m == 6 || m == 8; }
+// tile / kernel sizes the device kernels are instantiated for: n = m + r - 1 in {4, 6, 8, 10}
+static bool device_tile_ok(int m, int r)
+{
+    if (r == 3) return m == 2 || m == 4 || m == 6 || m == 8;
+    if (r == 5) return m == 2 || m == 4 || m == 6;
+    return false;
+}
 static bool dtype_ok(int dtype) { return dtype == NOVA_F16 || dtype == NOVA_F32; }
 
 static int check_handle(const nova_transforms *t)
 {
     if (!t) return NOVA_EINVAL;
-    if (t->r != 3 || !device_tile_ok(t->m)) return NOVA_EUNSUPPORTED;
+    if (!device_tile_ok(t->m, t->r)) return NOVA_EUNSUPPORTED;
     return NOVA_OK;
 }
 
@@ -53,32 +59,32 @@ constexpr size_t kDefaultSlabBytes = (size_t)256 << 20;
 
 using namespace nova;
 
-extern "C" size_t nova_filter_bytes(int K, int C, int m, int dtype)
+extern "C" size_t nova_filter_bytes(int K, int C, int m, int r, int dtype)
 {
-    if (K < 1 || C < 1 || m < 1 || !dtype_ok(dtype)) return 0;
-    const size_t n = (size_t)m + 2;
+    if (K < 1 || C < 1 || m < 1 || r < 1 || !dtype_ok(dtype)) return 0;
+    const size_t n = (size_t)m + r - 1;
     return n * n * ceil_div(C, kChanBlock) * ((size_t)ceil_div(K, kChanBlock) * kChanBlock) * kChanBlock *
            dtype_size(dtype);
 }
 
-extern "C" size_t nova_input_bytes(int N, int C, int H, int W, int m, int dtype)
+extern "C" size_t nova_input_bytes(int N, int C, int H, int W, int m, int r, int dtype)
 {
-    if (!dims_ok(N, C, H, W, 1) || m < 1 || !dtype_ok(dtype)) return 0;
-    return v_bytes(make_geometry(N, C, H, W, 1, m), dtype);
+    if (!dims_ok(N, C, H, W, 1) || m < 1 || r < 1 || !dtype_ok(dtype)) return 0;
+    return v_bytes(make_geometry(N, C, H, W, 1, m, r), dtype);
 }
 
-extern "C" size_t nova_product_bytes(int N, int K, int H, int W, int m, int dtype, int flags)
+extern "C" size_t nova_product_bytes(int N, int K, int H, int W, int m, int r, int dtype, int flags)
 {
-    if (!dims_ok(N, 1, H, W, K) || m < 1 || !dtype_ok(dtype)) return 0;
-    return m_bytes(make_geometry(N, 1, H, W, K, m), dtype, flags);
+    if (!dims_ok(N, 1, H, W, K) || m < 1 || r < 1 || !dtype_ok(dtype)) return 0;
+    return m_bytes(make_geometry(N, 1, H, W, K, m, r), dtype, flags);
 }
 
-extern "C" size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K, int m, int dtype, int flags,
-                                              int images_per_slab)
+extern "C" size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K, int m, int r, int dtype,
+                                              int flags, int images_per_slab)
 {
-    if (!dims_ok(N, C, H, W, K) || !device_tile_ok(m) || !dtype_ok(dtype) || images_per_slab < 0) return 0;
+    if (!dims_ok(N, C, H, W, K) || !device_tile_ok(m, r) || !dtype_ok(dtype) || images_per_slab < 0) return 0;
     auto slab_bytes = [&](long long count) {
-        const Geometry sg = make_geometry((int)count, C, H, W, K, m);
+        const Geometry sg = make_geometry((int)count, C, H, W, K, m, r);
         return align256(v_bytes(sg, dtype)) + align256(m_bytes(sg, dtype, flags));
     };
     long long imgs = images_per_slab;
@@ -107,7 +113,7 @@ extern "C" int nova_input_transform(const nova_transforms *t, const void *x, voi
 {
     if (int rc = check_handle(t)) return rc;
     if (!x || !V || !dims_ok(N, C, H, W, 1) || !dtype_ok(dtype)) return NOVA_EINVAL;
-    const Geometry g = make_geometry(N, C, H, W, 1, t->m);
+    const Geometry g = make_geometry(N, C, H, W, 1, t->m, t->r);
     if (V_bytes < v_bytes(g, dtype)) return NOVA_ENOSPC;
     return hip_result(launch_input_transform(t, x, V, g, dtype, stream));
 }
@@ -117,7 +123,7 @@ extern "C" int nova_contract(const nova_transforms *t, const void *U, const void
 {
     if (int rc = check_handle(t)) return rc;
     if (!U || !V || !M || !dims_ok(N, C, H, W, K) || !dtype_ok(dtype)) return NOVA_EINVAL;
-    const Geometry g = make_geometry(N, C, H, W, K, t->m);
+    const Geometry g = make_geometry(N, C, H, W, K, t->m, t->r);
     if (M_bytes < m_bytes(g, dtype, flags)) return NOVA_ENOSPC;
     return hip_result(launch_contract(t, U, V, M, g, dtype, flags, stream));
 }
@@ -127,7 +133,7 @@ extern "C" int nova_output_transform(const nova_transforms *t, const void *M, si
 {
     if (int rc = check_handle(t)) return rc;
     if (!M || !y || !dims_ok(N, 1, H, W, K) || !dtype_ok(dtype)) return NOVA_EINVAL;
-    const Geometry g = make_geometry(N, 1, H, W, K, t->m);
+    const Geometry g = make_geometry(N, 1, H, W, K, t->m, t->r);
     if (M_bytes < m_bytes(g, dtype, flags)) return NOVA_ENOSPC;
     return hip_result(launch_output_transform(t, M, y, g, dtype, flags, stream));
 }
@@ -139,11 +145,11 @@ extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, con
     if (int rc = check_handle(t)) return rc;
     if (!x || !U || !y || !workspace || !dims_ok(N, C, H, W, K) || !dtype_ok(dtype)) return NOVA_EINVAL;
     if (((uintptr_t)workspace & 255) != 0) return NOVA_EINVAL;
-    const int m = t->m;
+    const int m = t->m, r = t->r;
 
     // largest slab (whole images) whose V and M fit the workspace; slab_bytes grows with the count
     auto slab_bytes = [&](long long count, size_t *v_part) {
-        const Geometry sg = make_geometry((int)count, C, H, W, K, m);
+        const Geometry sg = make_geometry((int)count, C, H, W, K, m, r);
         const size_t vb = align256(v_bytes(sg, dtype));
         if (v_part) *v_part = vb;
         return vb + align256(m_bytes(sg, dtype, flags));
@@ -163,7 +169,7 @@ extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, con
     char *Mbuf = Vbuf + v_part;
     for (int n0 = 0; n0 < N; n0 += (int)imgs) {
         const int nb = (N - n0 < imgs) ? N - n0 : (int)imgs;
-        const Geometry g = make_geometry(nb, C, H, W, K, m);
+        const Geometry g = make_geometry(nb, C, H, W, K, m, r);
         const char *xs = (const char *)x + (size_t)n0 * C * H * W * es;
         char *ys = (char *)y + (size_t)n0 * K * H * W * es;
         if (int err = launch_input_transform(t, xs, Vbuf, g, dtype, stream)) return hip_result(err);

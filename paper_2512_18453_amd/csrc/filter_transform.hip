@@ -1,4 +1,5 @@
-// Filter transform U = G g G^T (Sec. 2.1 step 2, nested in 2D), one thread per (k, c) pair.
+// Filter transform U = G g G^T (Sec. 2.1 step 2, nested in 2D) of R x R kernels, one thread per
+// (k, c) pair.
 // Evaluated in binary64 with G rounded once to binary64, result rounded once to the storage
 // format, written in the channel-blocked layout U[xi][c/32][Kp][32] (zero in the padding).
 // Runs once per weight set, so it is written for exactness, not speed.
@@ -6,10 +7,10 @@
 
 namespace nova {
 
-template <int N, typename T>
+template <int N, int R, typename T>
 __global__ void __launch_bounds__(256)
 filter_transform_kernel(const T *__restrict__ w, T *__restrict__ U, int K, int C, int Kp, int c_blocks,
-                        FilterCoef<N> coef)
+                        FilterCoef<N, R> coef)
 {
     const long long total = (long long)c_blocks * Kp * kChanBlock;
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -25,19 +26,19 @@ filter_transform_kernel(const T *__restrict__ w, T *__restrict__ U, int K, int C
         for (int xi = 0; xi < N * N; ++xi) dst[xi * xi_stride] = (T)0.0f;
         return;
     }
-    double g[9];
-    const T *src = w + ((size_t)k * C + c) * 9;
+    double g[R * R];
+    const T *src = w + ((size_t)k * C + c) * (R * R);
 #pragma unroll
-    for (int i = 0; i < 9; ++i) g[i] = (double)load_f32(src + i);
+    for (int i = 0; i < R * R; ++i) g[i] = (double)load_f32(src + i);
 
-    double tmp[N][3];                     // G g
+    double tmp[N][R];                     // G g
 #pragma unroll
     for (int i = 0; i < N; ++i)
 #pragma unroll
-        for (int b = 0; b < 3; ++b) {
+        for (int b = 0; b < R; ++b) {
             double s = 0.0;
 #pragma unroll
-            for (int a = 0; a < 3; ++a) s += coef.g[i * 3 + a] * g[a * 3 + b];
+            for (int a = 0; a < R; ++a) s += coef.g[i * R + a] * g[a * R + b];
             tmp[i][b] = s;
         }
 #pragma unroll
@@ -46,21 +47,21 @@ filter_transform_kernel(const T *__restrict__ w, T *__restrict__ U, int K, int C
         for (int j = 0; j < N; ++j) {     // (G g) G^T
             double s = 0.0;
 #pragma unroll
-            for (int b = 0; b < 3; ++b) s += tmp[i][b] * coef.g[j * 3 + b];
+            for (int b = 0; b < R; ++b) s += tmp[i][b] * coef.g[j * R + b];
             dst[(size_t)(i * N + j) * xi_stride] = round_f64_to(s, (T *)nullptr);
         }
 }
 
-template <int N, typename T>
+template <int N, int R, typename T>
 static int launch_ft(const nova_transforms *t, const void *w, int K, int C, void *U, hipStream_t stream)
 {
-    FilterCoef<N> coef;
-    for (int i = 0; i < N * 3; ++i) coef.g[i] = t->G64[i];
+    FilterCoef<N, R> coef;
+    for (int i = 0; i < N * R; ++i) coef.g[i] = t->G64[i];
     const int c_blocks = ceil_div(C, kChanBlock);
     const int Kp = ceil_div(K, kChanBlock) * kChanBlock;
     const long long total = (long long)c_blocks * Kp * kChanBlock;
     const unsigned blocks = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL((filter_transform_kernel<N, T>), dim3(blocks), dim3(256), 0, stream,
+    hipLaunchKernelGGL((filter_transform_kernel<N, R, T>), dim3(blocks), dim3(256), 0, stream,
                        (const T *)w, (T *)U, K, C, Kp, c_blocks, coef);
     return (int)hipGetLastError();
 }
@@ -70,13 +71,21 @@ int launch_filter_transform(const nova_transforms *t, const void *w, int K, int 
 {
     hipStream_t s = (hipStream_t)stream;
     const bool h = dtype == NOVA_F16;
-    switch (t->n) {
-    case 4: return h ? launch_ft<4, f16>(t, w, K, C, U, s) : launch_ft<4, float>(t, w, K, C, U, s);
-    case 6: return h ? launch_ft<6, f16>(t, w, K, C, U, s) : launch_ft<6, float>(t, w, K, C, U, s);
-    case 8: return h ? launch_ft<8, f16>(t, w, K, C, U, s) : launch_ft<8, float>(t, w, K, C, U, s);
-    case 10: return h ? launch_ft<10, f16>(t, w, K, C, U, s) : launch_ft<10, float>(t, w, K, C, U, s);
-    default: return (int)hipErrorInvalidValue;
+    if (t->r == 3) {
+        switch (t->n) {
+        case 4: return h ? launch_ft<4, 3, f16>(t, w, K, C, U, s) : launch_ft<4, 3, float>(t, w, K, C, U, s);
+        case 6: return h ? launch_ft<6, 3, f16>(t, w, K, C, U, s) : launch_ft<6, 3, float>(t, w, K, C, U, s);
+        case 8: return h ? launch_ft<8, 3, f16>(t, w, K, C, U, s) : launch_ft<8, 3, float>(t, w, K, C, U, s);
+        case 10: return h ? launch_ft<10, 3, f16>(t, w, K, C, U, s) : launch_ft<10, 3, float>(t, w, K, C, U, s);
+        }
+    } else if (t->r == 5) {
+        switch (t->n) {
+        case 6: return h ? launch_ft<6, 5, f16>(t, w, K, C, U, s) : launch_ft<6, 5, float>(t, w, K, C, U, s);
+        case 8: return h ? launch_ft<8, 5, f16>(t, w, K, C, U, s) : launch_ft<8, 5, float>(t, w, K, C, U, s);
+        case 10: return h ? launch_ft<10, 5, f16>(t, w, K, C, U, s) : launch_ft<10, 5, float>(t, w, K, C, U, s);
+        }
     }
+    return (int)hipErrorInvalidValue;
 }
 
 }  // namespace nova

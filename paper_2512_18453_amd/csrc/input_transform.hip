@@ -3,7 +3,7 @@
 //
 // One workgroup takes one image, one tile row, a group of TWB neighbouring tiles and one block
 // of 32 channels (for narrow images, where a tile row has few tiles: TRB neighbouring tile rows
-// of full width).  The 32-channel x (TRB*m + 2 rows) x (TWB*m + 2 columns) input strip is staged in LDS
+// of full width).  The 32-channel x (TRB*m + r - 1 rows) x (TWB*m + r - 1 columns) input strip is staged in LDS
 // in the order it has in memory (16-byte pieces when W allows, all loads of a round in flight
 // together), with a channel pitch that puts the 32 channels of a half-wave into 32 different
 // banks for the per-thread tile reads (thread = one tile x one channel, 32 consecutive lanes =
@@ -76,7 +76,7 @@ template <int N> struct RowSplit { static constexpr int value = ((N / 2) % 2 == 
 struct StripShape {
     int twb;         // tiles per group (all tile rows of the group together)
     int trb;         // tile rows per group; > 1 only if a group spans the image width
-    int rows;        // strip rows = trb * m + 2
+    int rows;        // strip rows = trb * m + r - 1
     unsigned rows_magic;    // ceil(2^32 / rows)
     int groups;      // tile groups per tile row
     int pieces;      // 16-byte pieces per strip row (vector path) / columns per row (scalar path)
@@ -144,14 +144,15 @@ __device__ __forceinline__ void transform_rows_of_tile(const T *tile, int row_pi
     }
 }
 
-template <int N, typename T, bool SYM, int STG>
+template <int N, int R, typename T, bool SYM, int STG>
 __global__ void __launch_bounds__(512)
 input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H, int W,
                        int tiles_h, int tiles_w, int c_blocks, long long Ttot, long long x_elems,
                        StripShape sh, InCoef<N> coef)
 {
     constexpr bool VEC = STG == kStageVec;
-    constexpr int M = N - 2;
+    constexpr int M = N - R + 1;                 // outputs per tile side = tile stride
+    constexpr int PAD = (R - 1) / 2;             // zero border of the convolution
     constexpr int PE = 16 / (int)sizeof(T);      // elements per 16-byte piece
     constexpr int SP = RowSplit<N>::value;
     typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -168,22 +169,22 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
     const int img = bid;
 
     const int tc0 = sh.trb > 1 ? 0 : tg * sh.twb;
-    const int h_lo = tr * M - 1;          // image row of strip row 0
-    const int w_lo = tc0 * M - 1;         // first image column the group needs
+    const int h_lo = tr * M - PAD;        // image row of strip row 0
+    const int w_lo = tc0 * M - PAD;       // first image column the group needs
     int w_al = w_lo;                      // image column of strip column 0
 
     // ---- stage the strip [32 channels][N rows][columns] in the order it has in memory
     if constexpr (VEC) {
         // W is a multiple of PE and x is 16-byte aligned: every piece is wholly inside or outside
         // the image.  All loads of a round are issued before the first LDS write waits on them.
-        w_al = (w_lo + PE) / PE * PE - PE;        // floor to a multiple of PE (w_lo >= -1)
+        w_al = (w_lo + PE) / PE * PE - PE;        // floor to a multiple of PE (w_lo >= -PAD >= -PE)
         const int slots = kChanBlock * sh.rows * sh.pieces;
-        constexpr int R = 8;                      // usually the whole strip in one round trip
-        for (int base = threadIdx.x; base < slots; base += R * (int)blockDim.x) {
-            u32x4 val[R];
-            int dst[R];
+        constexpr int RT = 8;                      // usually the whole strip in one round trip
+        for (int base = threadIdx.x; base < slots; base += RT * (int)blockDim.x) {
+            u32x4 val[RT];
+            int dst[RT];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
+            for (int r = 0; r < RT; ++r) {
                 const int s = base + r * (int)blockDim.x;
                 const int line = (int)__umulhi((unsigned)s, sh.piece_magic);
                 const int q = s - line * sh.pieces;
@@ -195,7 +196,7 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
                 if (ok) val[r] = *reinterpret_cast<const u32x4 *>(x + (((size_t)img * C + c) * H + h) * W + w);
             }
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+            for (int r = 0; r < RT; ++r)
                 if (dst[r] >= 0) {
                     u32x2 *p = reinterpret_cast<u32x2 *>(lds + dst[r]);
                     p[0] = u32x2{val[r].x, val[r].y};
@@ -203,7 +204,7 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
                 }
         }
     } else if constexpr (STG == kStageFlat) {
-        // The group spans the image width (tc0 = 0, w_lo = -1).  Rows h0..h1 of one channel are one
+        // The group spans the image width (tc0 = 0, w_lo = -PAD).  Rows h0..h1 of one channel are one
         // run of (h1 - h0 + 1) * W elements; it is covered with 16-byte pieces aligned in x (their
         // ends may belong to neighbouring rows or channels: those elements are dropped), and every
         // element goes to its own (row, column) of the strip.  What the image does not cover
@@ -218,12 +219,12 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
         const int h1 = h_lo + sh.rows - 1 > H - 1 ? H - 1 : h_lo + sh.rows - 1;
         const int run = (h1 - h0 + 1) * W;
         const int slots = kChanBlock * sh.pieces;
-        constexpr int R = 4;
-        for (int base = threadIdx.x; base < slots; base += R * (int)blockDim.x) {
-            T val[R][PE];
-            int rel[R], c_of[R];
+        constexpr int RT = 4;
+        for (int base = threadIdx.x; base < slots; base += RT * (int)blockDim.x) {
+            T val[RT][PE];
+            int rel[RT], c_of[RT];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
+            for (int r = 0; r < RT; ++r) {
                 const int s = base + r * (int)blockDim.x;
                 const int c_in = (int)__umulhi((unsigned)s, sh.piece_magic);
                 const int k = s - c_in * sh.pieces;
@@ -249,12 +250,12 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
                 }
             }
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
+            for (int r = 0; r < RT; ++r) {
                 // (row, column) of the first element that belongs to the run, then step along it
                 int q = rel[r] < 0 ? 0 : rel[r];
                 int hr = (int)__umulhi((unsigned)q, sh.w_magic);
                 int w = q - hr * W;
-                T *row0 = lds + c_of[r] * sh.ch_pitch + (h0 - h_lo) * sh.row_pitch + 1;    // column of w = 0
+                T *row0 = lds + c_of[r] * sh.ch_pitch + (h0 - h_lo) * sh.row_pitch + PAD;  // column of w = 0
 #pragma unroll
                 for (int e = 0; e < PE; ++e) {
                     const int pos = rel[r] + e;
@@ -269,12 +270,12 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
         // any W: element-wise, lanes along W
         const int cols = sh.pieces;
         const int slots = kChanBlock * sh.rows * cols;
-        constexpr int R = 8;
-        for (int base = threadIdx.x; base < slots; base += R * (int)blockDim.x) {
-            T val[R];
-            int dst[R];
+        constexpr int RT = 8;
+        for (int base = threadIdx.x; base < slots; base += RT * (int)blockDim.x) {
+            T val[RT];
+            int dst[RT];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
+            for (int r = 0; r < RT; ++r) {
                 const int s = base + r * (int)blockDim.x;
                 const int line = (int)__umulhi((unsigned)s, sh.piece_magic);
                 const int q = s - line * cols;
@@ -286,7 +287,7 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
                 if (ok) val[r] = x[(((size_t)img * C + c) * H + h) * W + w];
             }
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+            for (int r = 0; r < RT; ++r)
                 if (dst[r] >= 0) lds[dst[r]] = val[r];
         }
     }
@@ -305,7 +306,7 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
     constexpr int ROWS_MAX = SP > N - SP ? SP : N - SP;
     T res[ROWS_MAX * N];
     if (active) {
-        constexpr bool AL = VEC && N == 10;       // window column 1 = image column 8*(tc0+j): 16-byte aligned
+        constexpr bool AL = VEC && N == 10 && R == 3;   // window column 1 = image column 8*(tc0+j): 16-byte aligned
         if (half == 0) transform_rows_of_tile<N, T, SYM, AL, 0, SP>(tile, sh.row_pitch, res, 1, coef);
         else           transform_rows_of_tile<N, T, SYM, AL, SP, N>(tile, sh.row_pitch, res, 1, coef);
     }
@@ -360,15 +361,15 @@ static void fill_in_coef(const nova_transforms *t, InCoef<N> &k)
 }
 
 // Strip geometry for groups of `trb` tile rows x `twb` tiles; returns the LDS bytes it needs.
-template <int N, typename T>
+template <int N, int R, typename T>
 static size_t strip_shape(int twb, int trb, bool vec, StripShape &sh)
 {
     sh.w_magic = 0;
-    constexpr int M = N - 2;
+    constexpr int M = N - R + 1;
     constexpr int PE = 16 / (int)sizeof(T);
-    const int need = twb * M + 2;                       // columns w_lo .. w_lo + need - 1
+    const int need = twb * M + R - 1;                   // columns w_lo .. w_lo + need - 1
     sh.trb = trb;
-    sh.rows = trb * M + 2;
+    sh.rows = trb * M + R - 1;
     sh.rows_magic = (unsigned)((((unsigned long long)1 << 32) + sh.rows - 1) / sh.rows);
     if (vec) {
         // worst-case offset of w_lo inside its piece is PE - 1
@@ -389,7 +390,7 @@ static size_t strip_shape(int twb, int trb, bool vec, StripShape &sh)
     return (size_t)kChanBlock * chp * sizeof(T);
 }
 
-template <int N, typename T>
+template <int N, int R, typename T>
 static int launch_it(const nova_transforms *t, const void *x, void *V, const Geometry &g, hipStream_t stream)
 {
     constexpr int PE = 16 / (int)sizeof(T);
@@ -400,7 +401,7 @@ static int launch_it(const nova_transforms *t, const void *x, void *V, const Geo
     // the strip, then the results [xi][tile][32], and may take at most 64 KiB
     StripShape sh;
     auto lds_need = [&](int twb, int trb) {
-        const size_t strip = strip_shape<N, T>(twb, trb, vec, sh);
+        const size_t strip = strip_shape<N, R, T>(twb, trb, vec, sh);
         const size_t out_stage = (size_t)N * N * twb * trb * kChanBlock * sizeof(T);
         return strip > out_stage ? strip : out_stage;
     };
@@ -430,11 +431,11 @@ static int launch_it(const nova_transforms *t, const void *x, void *V, const Geo
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
     void (*kern)(const T *, T *, int, int, int, int, int, int, long long, long long, StripShape, InCoef<N>);
     if (t->symmetric)
-        kern = vec ? input_transform_kernel<N, T, true, kStageVec>
-             : flat ? input_transform_kernel<N, T, true, kStageFlat> : input_transform_kernel<N, T, true, kStageScalar>;
+        kern = vec ? input_transform_kernel<N, R, T, true, kStageVec>
+             : flat ? input_transform_kernel<N, R, T, true, kStageFlat> : input_transform_kernel<N, R, T, true, kStageScalar>;
     else
-        kern = vec ? input_transform_kernel<N, T, false, kStageVec>
-             : flat ? input_transform_kernel<N, T, false, kStageFlat> : input_transform_kernel<N, T, false, kStageScalar>;
+        kern = vec ? input_transform_kernel<N, R, T, false, kStageVec>
+             : flat ? input_transform_kernel<N, R, T, false, kStageFlat> : input_transform_kernel<N, R, T, false, kStageScalar>;
     const long long x_elems = (long long)g.N * g.C * g.H * g.W;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(threads), lds_bytes, stream,
                        (const T *)x, (T *)V, g.C, g.H, g.W, g.tiles_h, g.tiles_w, g.c_blocks, g.T, x_elems, sh, coef);
@@ -446,13 +447,21 @@ int launch_input_transform(const nova_transforms *t, const void *x, void *V, con
 {
     hipStream_t s = (hipStream_t)stream;
     const bool h = dtype == NOVA_F16;
-    switch (t->n) {
-    case 4: return h ? launch_it<4, f16>(t, x, V, g, s) : launch_it<4, float>(t, x, V, g, s);
-    case 6: return h ? launch_it<6, f16>(t, x, V, g, s) : launch_it<6, float>(t, x, V, g, s);
-    case 8: return h ? launch_it<8, f16>(t, x, V, g, s) : launch_it<8, float>(t, x, V, g, s);
-    case 10: return h ? launch_it<10, f16>(t, x, V, g, s) : launch_it<10, float>(t, x, V, g, s);
-    default: return (int)hipErrorInvalidValue;
+    if (t->r == 3) {
+        switch (t->n) {
+        case 4: return h ? launch_it<4, 3, f16>(t, x, V, g, s) : launch_it<4, 3, float>(t, x, V, g, s);
+        case 6: return h ? launch_it<6, 3, f16>(t, x, V, g, s) : launch_it<6, 3, float>(t, x, V, g, s);
+        case 8: return h ? launch_it<8, 3, f16>(t, x, V, g, s) : launch_it<8, 3, float>(t, x, V, g, s);
+        case 10: return h ? launch_it<10, 3, f16>(t, x, V, g, s) : launch_it<10, 3, float>(t, x, V, g, s);
+        }
+    } else if (t->r == 5) {
+        switch (t->n) {
+        case 6: return h ? launch_it<6, 5, f16>(t, x, V, g, s) : launch_it<6, 5, float>(t, x, V, g, s);
+        case 8: return h ? launch_it<8, 5, f16>(t, x, V, g, s) : launch_it<8, 5, float>(t, x, V, g, s);
+        case 10: return h ? launch_it<10, 5, f16>(t, x, V, g, s) : launch_it<10, 5, float>(t, x, V, g, s);
+        }
     }
+    return (int)hipErrorInvalidValue;
 }
 
 }  // namespace nova

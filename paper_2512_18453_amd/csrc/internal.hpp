@@ -32,25 +32,25 @@ struct InCoef {
     float inf[H + 1];
 };
 
-// Coefficients of one 1D output transform: A (N x M) row-major, and for the symmetric case
-// pw[j][i] = A[row of +a_j][i] (a_j^i times the row's scale), zero = A[row of 0][0],
-// inf = A[row of infinity][M-1] (both 1 unless the rows are rescaled).
-template <int N>
+// Coefficients of one 1D output transform for kernel size R: A (N x M) row-major, M = N - R + 1,
+// and for the symmetric case pw[j][i] = A[row of +a_j][i] (a_j^i times the row's scale),
+// zero = A[row of 0][0], inf = A[row of infinity][M-1] (both 1 unless the rows are rescaled).
+template <int N, int R>
 struct OutCoef {
-    static constexpr int M = N - 2;
+    static constexpr int M = N - R + 1;
     static constexpr int H = (N - 2) / 2;
     float a[N * M];
     float pw[H > 0 ? H * M : 1];
     float zero, inf;
 };
 
-template <int N>
+template <int N, int R>
 struct FilterCoef {
-    double g[N * 3];
+    double g[N * R];
 };
 
 struct Geometry {
-    int N, C, H, W, K, m, n;
+    int N, C, H, W, K, m, r, n;
     int tiles_h, tiles_w;
     long long T;          // tiles in the batch
     long long Tp;         // T rounded up to a multiple of 128: row count of M (rows >= T are scratch)
@@ -60,10 +60,10 @@ struct Geometry {
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-inline Geometry make_geometry(int N, int C, int H, int W, int K, int m)
+inline Geometry make_geometry(int N, int C, int H, int W, int K, int m, int r)
 {
     Geometry g;
-    g.N = N; g.C = C; g.H = H; g.W = W; g.K = K; g.m = m; g.n = m + 2;
+    g.N = N; g.C = C; g.H = H; g.W = W; g.K = K; g.m = m; g.r = r; g.n = m + r - 1;
     g.tiles_h = ceil_div(H, m);
     g.tiles_w = ceil_div(W, m);
     g.T = (long long)N * g.tiles_h * g.tiles_w;

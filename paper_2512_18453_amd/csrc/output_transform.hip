@@ -16,10 +16,10 @@
 
 namespace nova {
 
-template <int N, bool SYM>
-__device__ __forceinline__ void output_transform_1d(const float (&v)[N], float (&out)[N - 2], const OutCoef<N> &k)
+template <int N, int R, bool SYM>
+__device__ __forceinline__ void output_transform_1d(const float (&v)[N], float (&out)[N - R + 1], const OutCoef<N, R> &k)
 {
-    constexpr int M = N - 2;
+    constexpr int M = N - R + 1;
     constexpr int H = (N - 2) / 2;
     if constexpr (SYM) {
         float s[H > 0 ? H : 1], d[H > 0 ? H : 1];
@@ -71,13 +71,13 @@ struct OutShape {
 //                 whatever W is (element stores at its two ragged ends)
 enum { kStoreScalar = 0, kStoreVec = 1, kStoreFlat = 2 };
 
-template <int N, typename T, typename MT, bool SYM, int STG, bool RELU>
+template <int N, int R, typename T, typename MT, bool SYM, int STG, bool RELU>
 __global__ void __launch_bounds__(512)
 output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int H, int W,
                         int tiles_h, int tiles_w, int k_blocks, long long Ttot, OutShape sh,
-                        OutCoef<N> coef)
+                        OutCoef<N, R> coef)
 {
-    constexpr int M = N - 2;
+    constexpr int M = N - R + 1;
     constexpr int PE = 16 / (int)sizeof(T);
     typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -108,7 +108,7 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
             float v[N], o[M];
 #pragma unroll
             for (int a = 0; a < N; ++a) v[a] = (float)*plane_element(Mp + (size_t)(a * N + b) * xi_stride, in_plane);
-            output_transform_1d<N, SYM>(v, o, coef);
+            output_transform_1d<N, R, SYM>(v, o, coef);
 #pragma unroll
             for (int p = 0; p < M; ++p) z[p][b] = o[p];
         }
@@ -116,7 +116,7 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
 #pragma unroll
         for (int p = 0; p < M; ++p) {
             float o[M];
-            output_transform_1d<N, SYM>(z[p], o, coef);
+            output_transform_1d<N, R, SYM>(z[p], o, coef);
 #pragma unroll
             for (int q = 0; q < M; ++q) {
                 float val = o[q];
@@ -201,10 +201,10 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
     }
 }
 
-template <int N>
-static void fill_out_coef(const nova_transforms *t, OutCoef<N> &k)
+template <int N, int R>
+static void fill_out_coef(const nova_transforms *t, OutCoef<N, R> &k)
 {
-    constexpr int M = N - 2, H = OutCoef<N>::H;
+    constexpr int M = N - R + 1, H = OutCoef<N, R>::H;
     for (int i = 0; i < N * M; ++i) k.a[i] = t->A32[i];
     for (int j = 0; j < H; ++j)
         for (int i = 0; i < M; ++i) k.pw[j * M + i] = t->A32[(2 * j + 1) * M + i];
@@ -212,10 +212,10 @@ static void fill_out_coef(const nova_transforms *t, OutCoef<N> &k)
     k.inf = t->A32[(N - 1) * M + (M - 1)];
 }
 
-template <int N, typename T>
+template <int N, int R, typename T>
 static size_t out_shape(int twb, int trb, OutShape &sh)
 {
-    constexpr int M = N - 2;
+    constexpr int M = N - R + 1;
     sh.twb = twb * trb;
     sh.trb = trb;
     sh.rows = trb * M;
@@ -230,17 +230,17 @@ static size_t out_shape(int twb, int trb, OutShape &sh)
     return (size_t)kChanBlock * kp * sizeof(T);
 }
 
-template <int N, typename T, typename MT>
+template <int N, int R, typename T, typename MT>
 static int launch_ot(const nova_transforms *t, const void *Mp, void *y, const Geometry &g, int flags,
                      hipStream_t stream)
 {
-    constexpr int M = N - 2;
+    constexpr int M = N - R + 1;
     constexpr int PE = 16 / (int)sizeof(T);
-    OutCoef<N> coef;
-    fill_out_coef<N>(t, coef);
+    OutCoef<N, R> coef;
+    fill_out_coef<N, R>(t, coef);
     OutShape sh;
     int twb_max = 16;
-    while (twb_max > 1 && out_shape<N, T>(twb_max, 1, sh) > 64 * 1024) --twb_max;
+    while (twb_max > 1 && out_shape<N, R, T>(twb_max, 1, sh) > 64 * 1024) --twb_max;
     sh.groups = ceil_div(g.tiles_w, twb_max);
     const int twb = ceil_div(g.tiles_w, sh.groups);     // tiles of one tile row per group
     // narrow images: a group spans the width; give it as many tile rows as keep it within 8 tiles
@@ -250,10 +250,10 @@ static int launch_ot(const nova_transforms *t, const void *Mp, void *y, const Ge
         trb = 8 / twb;
         if (trb < 1) trb = 1;
         if (trb > g.tiles_h) trb = g.tiles_h;
-        while (trb > 1 && out_shape<N, T>(twb, trb, sh) > 64 * 1024) --trb;
+        while (trb > 1 && out_shape<N, R, T>(twb, trb, sh) > 64 * 1024) --trb;
     }
     trb = ceil_div(g.tiles_h, ceil_div(g.tiles_h, trb));    // same number of groups, evenly sized
-    const size_t lds_bytes = out_shape<N, T>(twb, trb, sh);     // (leaves sh.groups alone)
+    const size_t lds_bytes = out_shape<N, R, T>(twb, trb, sh);     // (leaves sh.groups alone)
     if (lds_bytes > 64 * 1024) return (int)hipErrorInvalidValue;
     if ((size_t)g.k_blocks * g.Tp * kChanBlock * sizeof(MT) >= ((size_t)1 << 32)) return (int)hipErrorInvalidValue;
     const bool aligned = ((uintptr_t)y % 16) == 0;
@@ -267,15 +267,15 @@ static int launch_ot(const nova_transforms *t, const void *Mp, void *y, const Ge
     const int threads = ((sh.twb * 32 + 63) / 64) * 64;
     const long long blocks = (long long)sh.groups * ceil_div(g.tiles_h, trb) * g.k_blocks * g.N;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
-    void (*kern)(const MT *, T *, int, int, int, int, int, int, long long, OutShape, OutCoef<N>);
+    void (*kern)(const MT *, T *, int, int, int, int, int, int, long long, OutShape, OutCoef<N, R>);
     const bool relu = (flags & NOVA_FLAG_RELU) != 0;
     const int stg = vec ? kStoreVec : flat ? kStoreFlat : kStoreScalar;
     auto pick = [&](auto sym) {
         constexpr bool S = decltype(sym)::value;
         switch (stg) {
-        case kStoreVec:  return relu ? output_transform_kernel<N, T, MT, S, kStoreVec, true> : output_transform_kernel<N, T, MT, S, kStoreVec, false>;
-        case kStoreFlat: return relu ? output_transform_kernel<N, T, MT, S, kStoreFlat, true> : output_transform_kernel<N, T, MT, S, kStoreFlat, false>;
-        default:         return relu ? output_transform_kernel<N, T, MT, S, kStoreScalar, true> : output_transform_kernel<N, T, MT, S, kStoreScalar, false>;
+        case kStoreVec:  return relu ? output_transform_kernel<N, R, T, MT, S, kStoreVec, true> : output_transform_kernel<N, R, T, MT, S, kStoreVec, false>;
+        case kStoreFlat: return relu ? output_transform_kernel<N, R, T, MT, S, kStoreFlat, true> : output_transform_kernel<N, R, T, MT, S, kStoreFlat, false>;
+        default:         return relu ? output_transform_kernel<N, R, T, MT, S, kStoreScalar, true> : output_transform_kernel<N, R, T, MT, S, kStoreScalar, false>;
         }
     };
     kern = t->symmetric ? pick(std::true_type{}) : pick(std::false_type{});
@@ -284,26 +284,34 @@ static int launch_ot(const nova_transforms *t, const void *Mp, void *y, const Ge
     return (int)hipGetLastError();
 }
 
-template <int N>
+template <int N, int R>
 static int launch_ot_n(const nova_transforms *t, const void *Mp, void *y, const Geometry &g, int dtype,
                        int flags, hipStream_t s)
 {
-    if (dtype == NOVA_F32) return launch_ot<N, float, float>(t, Mp, y, g, flags, s);
-    if (flags & NOVA_FLAG_M_F16) return launch_ot<N, f16, f16>(t, Mp, y, g, flags, s);
-    return launch_ot<N, f16, float>(t, Mp, y, g, flags, s);
+    if (dtype == NOVA_F32) return launch_ot<N, R, float, float>(t, Mp, y, g, flags, s);
+    if (flags & NOVA_FLAG_M_F16) return launch_ot<N, R, f16, f16>(t, Mp, y, g, flags, s);
+    return launch_ot<N, R, f16, float>(t, Mp, y, g, flags, s);
 }
 
 int launch_output_transform(const nova_transforms *t, const void *Mp, void *y, const Geometry &g,
                             int dtype, int flags, void *stream)
 {
     hipStream_t s = (hipStream_t)stream;
-    switch (t->n) {
-    case 4: return launch_ot_n<4>(t, Mp, y, g, dtype, flags, s);
-    case 6: return launch_ot_n<6>(t, Mp, y, g, dtype, flags, s);
-    case 8: return launch_ot_n<8>(t, Mp, y, g, dtype, flags, s);
-    case 10: return launch_ot_n<10>(t, Mp, y, g, dtype, flags, s);
-    default: return (int)hipErrorInvalidValue;
+    if (t->r == 3) {
+        switch (t->n) {
+        case 4: return launch_ot_n<4, 3>(t, Mp, y, g, dtype, flags, s);
+        case 6: return launch_ot_n<6, 3>(t, Mp, y, g, dtype, flags, s);
+        case 8: return launch_ot_n<8, 3>(t, Mp, y, g, dtype, flags, s);
+        case 10: return launch_ot_n<10, 3>(t, Mp, y, g, dtype, flags, s);
+        }
+    } else if (t->r == 5) {
+        switch (t->n) {
+        case 6: return launch_ot_n<6, 5>(t, Mp, y, g, dtype, flags, s);
+        case 8: return launch_ot_n<8, 5>(t, Mp, y, g, dtype, flags, s);
+        case 10: return launch_ot_n<10, 5>(t, Mp, y, g, dtype, flags, s);
+        }
     }
+    return (int)hipErrorInvalidValue;
 }
 
 }  // namespace nova

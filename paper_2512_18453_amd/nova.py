@@ -64,13 +64,13 @@ def lib():
         L.nova_get_matrix_f64.argtypes = [vp, i, ctypes.POINTER(ctypes.c_double)]
         L.nova_get_matrix_f32.argtypes = [vp, i, ctypes.POINTER(ctypes.c_float)]
         L.nova_kappa.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
-        L.nova_filter_bytes.argtypes = [i, i, i, i]
+        L.nova_filter_bytes.argtypes = [i] * 5
         L.nova_filter_bytes.restype = sz
-        L.nova_input_bytes.argtypes = [i] * 6
+        L.nova_input_bytes.argtypes = [i] * 7
         L.nova_input_bytes.restype = sz
-        L.nova_product_bytes.argtypes = [i] * 7
+        L.nova_product_bytes.argtypes = [i] * 8
         L.nova_product_bytes.restype = sz
-        L.nova_conv2d_workspace_bytes.argtypes = [i] * 9
+        L.nova_conv2d_workspace_bytes.argtypes = [i] * 10
         L.nova_conv2d_workspace_bytes.restype = sz
         L.nova_filter_transform.argtypes = [vp, vp, i, i, i, vp, vp]
         L.nova_winograd_conv2d.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp]
@@ -223,28 +223,30 @@ def nova_kappa(t):
     return dict(V=out[0], A=out[1], B=out[2], G=out[3])
 
 
-def nova_filter_bytes(K, C, m, dtype):
-    return lib().nova_filter_bytes(K, C, m, dtype)
+def nova_filter_bytes(K, C, m, dtype, r=3):
+    return lib().nova_filter_bytes(K, C, m, r, dtype)
 
 
-def nova_input_bytes(N, C, H, W, m, dtype):
-    return lib().nova_input_bytes(N, C, H, W, m, dtype)
+def nova_input_bytes(N, C, H, W, m, dtype, r=3):
+    return lib().nova_input_bytes(N, C, H, W, m, r, dtype)
 
 
-def nova_product_bytes(N, K, H, W, m, dtype, flags=0):
-    return lib().nova_product_bytes(N, K, H, W, m, dtype, flags)
+def nova_product_bytes(N, K, H, W, m, dtype, flags=0, r=3):
+    return lib().nova_product_bytes(N, K, H, W, m, r, dtype, flags)
 
 
-def nova_conv2d_workspace_bytes(N, C, H, W, K, m, dtype, flags=0, images_per_slab=0):
-    return lib().nova_conv2d_workspace_bytes(N, C, H, W, K, m, dtype, flags, images_per_slab)
+def nova_conv2d_workspace_bytes(N, C, H, W, K, m, dtype, flags=0, images_per_slab=0, r=3):
+    return lib().nova_conv2d_workspace_bytes(N, C, H, W, K, m, r, dtype, flags, images_per_slab)
 
 
 def nova_filter_transform(t, w, U=None):
-    """w [K,C,3,3] device tensor -> U (flat device tensor of the same dtype)."""
+    """w [K,C,r,r] device tensor -> U (flat device tensor of the same dtype)."""
     K, C = w.shape[0], w.shape[1]
+    if tuple(w.shape[2:]) != (t.r, t.r):
+        raise ValueError(f"filter is {tuple(w.shape[2:])}, the transforms are for {t.r} x {t.r}")
     dt = _dtype_code(w)
     if U is None:
-        U = torch.empty(nova_filter_bytes(K, C, t.m, dt) // w.element_size(), dtype=w.dtype, device=w.device)
+        U = torch.empty(nova_filter_bytes(K, C, t.m, dt, t.r) // w.element_size(), dtype=w.dtype, device=w.device)
     _check(lib().nova_filter_transform(t.handle, _dev(w), K, C, dt, _dev(U), _stream()), "nova_filter_transform")
     return U
 
@@ -256,7 +258,7 @@ def nova_winograd_conv2d(t, x, U, K, y=None, flags=0, workspace=None, images_per
     if y is None:
         y = torch.empty((N, K, H, W), dtype=x.dtype, device=x.device)
     if workspace is None:
-        workspace = torch.empty(nova_conv2d_workspace_bytes(N, C, H, W, K, t.m, dt, flags, images_per_slab),
+        workspace = torch.empty(nova_conv2d_workspace_bytes(N, C, H, W, K, t.m, dt, flags, images_per_slab, t.r),
                                 dtype=torch.uint8, device=x.device)
     _check(lib().nova_winograd_conv2d(t.handle, _dev(x), _dev(U), _dev(y), N, C, H, W, K, dt, flags,
                                       _dev(workspace), workspace.numel(), _stream()), "nova_winograd_conv2d")
@@ -267,7 +269,7 @@ def nova_input_transform(t, x, V=None):
     N, C, H, W = x.shape
     dt = _dtype_code(x)
     if V is None:
-        V = torch.empty(nova_input_bytes(N, C, H, W, t.m, dt) // x.element_size(), dtype=x.dtype, device=x.device)
+        V = torch.empty(nova_input_bytes(N, C, H, W, t.m, dt, t.r) // x.element_size(), dtype=x.dtype, device=x.device)
     _check(lib().nova_input_transform(t.handle, _dev(x), _dev(V), V.numel() * V.element_size(), N, C, H, W, dt,
                                       _stream()), "nova_input_transform")
     return V
@@ -277,7 +279,7 @@ def nova_contract(t, U, V, N, C, H, W, K, flags=0, M=None):
     dt = _dtype_code(V)
     if M is None:
         m_dtype = torch.float16 if (dt == NOVA_F16 and flags & NOVA_FLAG_M_F16) else torch.float32
-        nbytes = nova_product_bytes(N, K, H, W, t.m, dt, flags)
+        nbytes = nova_product_bytes(N, K, H, W, t.m, dt, flags, t.r)
         M = torch.empty(nbytes // (2 if m_dtype == torch.float16 else 4), dtype=m_dtype, device=V.device)
     _check(lib().nova_contract(t.handle, _dev(U), _dev(V), _dev(M), M.numel() * M.element_size(), N, C, H, W, K, dt,
                                flags, _stream()), "nova_contract")

@@ -544,3 +544,63 @@ def test_vgg_stack_full_size_sampled_images(m):
         else:
             act = y
         del y
+
+
+# 5 x 5 kernels (Sec. "Extension to 5 x 5 Kernels"): F(m, 5) needs m + 3 finite points -- the same
+# sets as F(m + 2, 3)
+R5_CASES = [
+    # m, points (name, size they are listed under), N, C, K, H, W
+    (2, ("standard", 4), 2, 8, 8, 7, 9),
+    (2, ("nova", 4), 1, 40, 33, 16, 24),
+    (4, ("standard", 6), 2, 24, 40, 19, 14),
+    (4, ("nova", 6), 2, 64, 64, 24, 32),
+    (4, ("nova", 6), 1, 5, 3, 13, 70),
+    (6, ("nova", 8), 2, 64, 128, 36, 48),
+    (6, ("nova", 8), 3, 33, 20, 17, 23),
+]
+
+
+def make_layer_r5(N, C, K, H, W, seed, dtype):
+    rng = np.random.default_rng(seed)
+    x = np.abs(rng.standard_normal((N, C, H, W))).astype(dtype)
+    w = (rng.standard_normal((K, C, 5, 5)) * np.sqrt(2.0 / (25.0 * C))).astype(dtype)
+    return x, w
+
+
+@pytest.mark.parametrize("m,pset,N,C,K,H,W", R5_CASES)
+def test_r5_fp16_stages_against_emulation(m, pset, N, C, K, H, W):
+    say(f"[case] fp16 stages F({m},5) points {pset} N={N} C={C} K={K} H={H} W={W}")
+    points = synth.point_set(*pset)
+    x, w = make_layer_r5(N, C, K, H, W, 900 + 10 * m + C, np.float16)
+    t = nova.nova_make_transforms(points, m, 5)
+    assert (t.n, t.r, t.symmetric) == (m + 4, 5, True)
+    got = run_stages(t, x, w)
+    x64, w64 = x.astype(np.float64), w.astype(np.float64)
+    y_o, U_o, V_o, M_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=16, want_intermediates=True)
+    same(got["U"], U_o, "U")
+    same(got["V"], V_o, "V")
+    assert rel_l2(got["M"], M_o) < 1e-5
+    assert np.array_equal(got["y"], got["y_conv"])
+    err = rel_l2(got["y"], y_o)
+    say(f"  rel-L2 vs emulation {err:.3e}; vs fp64 definition {rel_l2(got['y'], conv.direct_conv2d(x64, w64)):.3e}")
+    assert err < 5e-3
+
+
+@pytest.mark.parametrize("m,pset", [(2, ("standard", 4)), (4, ("nova", 6)), (6, ("nova", 8))])
+def test_r5_fp32_against_definition(m, pset):
+    say(f"[case] fp32 F({m},5) points {pset}")
+    points = synth.point_set(*pset)
+    x, w = make_layer_r5(2, 20, 12, 3 * m + 2, 5 * m - 1, 950 + m, np.float32)
+    x = (x * np.sign(np.random.default_rng(m).standard_normal(x.shape))).astype(np.float32)
+    t = nova.nova_make_transforms(points, m, 5)
+    got = run_stages(t, x, w)
+    x64, w64 = x.astype(np.float64), w.astype(np.float64)
+    want = conv.direct_conv2d(x64, w64)
+    y_o, U_o, V_o, _ = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=32, want_intermediates=True)
+    same(got["U"], U_o, "U")
+    same(got["V"], V_o, "V")
+    own, err = rel_l2(y_o, want), rel_l2(got["y"], y_o)
+    say(f"  emulation vs definition {own:.3e}; gpu vs emulation {err:.3e}; gpu vs definition {rel_l2(got['y'], want):.3e}")
+    assert err <= max(1e-5, 4 * own)
+    if m == 2:
+        assert rel_l2(got["y"], want) <= 1e-5 and np.abs(got["y"] - want).max() <= 1e-4

@@ -154,9 +154,13 @@ def test_error_codes():
     # device entry points reject bad arguments before touching the GPU
     t = nova.nova_make_transforms(synth.STANDARD[4], 4, 3)
     assert L.nova_winograd_conv2d(t.handle, None, None, None, 1, 1, 1, 1, 1, 0, 0, None, 0, None) == -1
-    t5 = nova.nova_make_transforms([0, 1, -1, 2, -2, 3, -3], 4, 5)
-    assert L.nova_filter_transform(t5.handle, 1, 1, 1, 0, 1, None) == -6      # r = 5: host only
-    assert L.nova_conv2d_workspace_bytes(1, 1, 1, 1, 1, 5, 0, 0, 0) == 0
+    t7 = nova.nova_make_transforms([0, 1, -1, 2, -2, 3, -3], 2, 7)
+    assert L.nova_filter_transform(t7.handle, 1, 1, 1, 0, 1, None) == -6      # r = 7: host only
+    t85 = nova.nova_make_transforms([0, 1, -1, 2, -2, 3, -3, 4, -4, 5, -5], 8, 5)
+    assert L.nova_filter_transform(t85.handle, 1, 1, 1, 0, 1, None) == -6     # F(8,5): n = 12, host only
+    assert L.nova_conv2d_workspace_bytes(1, 1, 1, 1, 1, 5, 3, 0, 0, 0) == 0   # m = 5
+    assert L.nova_conv2d_workspace_bytes(1, 1, 1, 1, 1, 8, 5, 0, 0, 0) == 0   # F(8,5)
+    assert L.nova_conv2d_workspace_bytes(1, 1, 1, 1, 1, 6, 5, 0, 0, 0) > 0    # F(6,5): n = 10
 
 
 def test_extended_constructor_rejects_bad_options():
@@ -188,6 +192,10 @@ def test_sizes_follow_documented_layouts():
     assert one == 100 * 8 * 49 * 32 * 2 + 100 * 8 * 128 * 32 * 4
     default = nova.nova_conv2d_workspace_bytes(32, 256, 56, 56, 256, 8, nova.NOVA_F16, 0, 0)
     assert default == whole
+    # 5 x 5 kernels: n = m + 4, tiles still at stride m
+    assert nova.nova_filter_bytes(64, 64, 4, nova.NOVA_F16, r=5) == 64 * 2 * 64 * 32 * 2
+    assert nova.nova_input_bytes(2, 64, 9, 13, 6, nova.NOVA_F16, r=5) == 100 * 2 * 12 * 32 * 2       # T = 2*2*3
+    assert nova.nova_product_bytes(2, 40, 9, 13, 6, nova.NOVA_F16, r=5) == 100 * 2 * 128 * 32 * 4
 
 
 @pytest.mark.parametrize("m,r,d_max", [(2, 3, 3), (2, 3, 10), (3, 3, 4), (4, 3, 6), (4, 3, 10), (5, 3, 5), (6, 3, 6),
