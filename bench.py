@@ -47,8 +47,8 @@ def main():
                     help="also run a plain 256 MiB device copy, the yardstick for rocprofv3's FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (the path shards by batch with no exchange; "
-                 "see DESIGN.md) -- use --gpus 1")
+        sys.exit("bench.py: this build runs on one GPU only (the path would shard by batch, with no "
+                 "exchange between GPUs) -- use --gpus 1")
 
     import numpy as np
     import torch
