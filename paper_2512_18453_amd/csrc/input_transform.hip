@@ -84,6 +84,7 @@ struct StripShape {
     int ch_pitch;    // elements
     unsigned piece_magic;   // ceil(2^32 / pieces): s / pieces == mulhi(s, magic) while s * pieces < 2^32
     unsigned w_magic;       // the same for W (flat staging)
+    int step_q, step_a, step_c;   // the workgroup size B as digits: B = (step_c * rows + step_a) * pieces + step_q
 };
 
 // How the strip gets into LDS.
@@ -178,27 +179,49 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
         // W is a multiple of PE and x is 16-byte aligned: every piece is wholly inside or outside
         // the image.  All loads of a round are issued before the first LDS write waits on them.
         w_al = (w_lo + PE) / PE * PE - PE;        // floor to a multiple of PE (w_lo >= -PAD >= -PE)
-        const int slots = kChanBlock * sh.rows * sh.pieces;
+        // Slot s = (c_in * rows + a) * pieces + q.  A thread takes s = tid, tid + B, tid + 2B, ..
+        // (B = workgroup size): its digits (c_in, a, q) are decoded once and then advanced by the
+        // digits of B (sh.step_*) with carries, and the LDS position and the offset in x move along
+        // with them: a few additions per piece instead of divisions and multiplications.
+        int line = (int)__umulhi(threadIdx.x, sh.piece_magic);
+        int q = (int)threadIdx.x - line * sh.pieces;
+        int c_in = (int)__umulhi((unsigned)line, sh.rows_magic), a = line - c_in * sh.rows;
+        // what of the strip lies inside the image: rows a_lo .. a_hi-1, pieces q_lo .. q_hi-1, channels < c_lim
+        const int a_lo = h_lo < 0 ? -h_lo : 0, a_hi = H - h_lo < sh.rows ? H - h_lo : sh.rows;
+        const int q_lo = w_al < 0 ? (-w_al) / PE : 0, q_hi = (W - w_al) / PE < sh.pieces ? (W - w_al) / PE : sh.pieces;
+        const int c_lim = C - cb * kChanBlock < kChanBlock ? C - cb * kChanBlock : kChanBlock;
+        const unsigned a_span = (unsigned)(a_hi - a_lo), q_span = (unsigned)(q_hi - q_lo);
+        // uniform base of this channel block's first plane + 32-bit element offset (the launcher checks the range)
+        const T *blk = x + ((size_t)img * C + (size_t)cb * kChanBlock) * H * W;
+        const int HW = H * W;
+        int dst = c_in * sh.ch_pitch + a * sh.row_pitch + q * PE;                 // LDS element
+        int off = c_in * HW + (h_lo + a) * W + w_al + q * PE;                     // element of blk (if inside)
+        const int dst_step = sh.step_c * sh.ch_pitch + sh.step_a * sh.row_pitch + sh.step_q * PE;
+        const int off_step = sh.step_c * HW + sh.step_a * W + sh.step_q * PE;
+        const int dst_wrap_q = sh.row_pitch - sh.pieces * PE, off_wrap_q = W - sh.pieces * PE;
+        const int dst_wrap_a = sh.ch_pitch - sh.rows * sh.row_pitch, off_wrap_a = HW - sh.rows * W;
         constexpr int RT = 8;                      // usually the whole strip in one round trip
-        for (int base = threadIdx.x; base < slots; base += RT * (int)blockDim.x) {
+        while (__builtin_amdgcn_readfirstlane(c_in) < kChanBlock) {       // lane 0 of a wave holds its lowest slot
             u32x4 val[RT];
-            int dst[RT];
+            int where[RT];
 #pragma unroll
             for (int r = 0; r < RT; ++r) {
-                const int s = base + r * (int)blockDim.x;
-                const int line = (int)__umulhi((unsigned)s, sh.piece_magic);
-                const int q = s - line * sh.pieces;
-                const int c_in = (int)__umulhi((unsigned)line, sh.rows_magic), a = line - c_in * sh.rows;
-                const int c = cb * kChanBlock + c_in, h = h_lo + a, w = w_al + q * PE;
-                const bool ok = s < slots && c < C && h >= 0 && h < H && w >= 0 && w < W;
-                dst[r] = s < slots ? c_in * sh.ch_pitch + a * sh.row_pitch + q * PE : -1;
+                where[r] = -1;
                 val[r] = u32x4{0u, 0u, 0u, 0u};
-                if (ok) val[r] = *reinterpret_cast<const u32x4 *>(x + (((size_t)img * C + c) * H + h) * W + w);
+                if (__builtin_amdgcn_readfirstlane(c_in) < kChanBlock) {  // uniform: skip rounds past the strip
+                    if (c_in < kChanBlock) where[r] = dst;
+                    const bool ok = c_in < c_lim && (unsigned)(a - a_lo) < a_span && (unsigned)(q - q_lo) < q_span;
+                    if (ok)
+                        val[r] = *reinterpret_cast<const NOVA_GLOBAL u32x4 *>(plane_element(blk, (unsigned)off * (unsigned)sizeof(T)));
+                    q += sh.step_q; a += sh.step_a; c_in += sh.step_c; dst += dst_step; off += off_step;
+                    if (q >= sh.pieces) { q -= sh.pieces; ++a; dst += dst_wrap_q; off += off_wrap_q; }
+                    if (a >= sh.rows) { a -= sh.rows; ++c_in; dst += dst_wrap_a; off += off_wrap_a; }
+                }
             }
 #pragma unroll
             for (int r = 0; r < RT; ++r)
-                if (dst[r] >= 0) {
-                    u32x2 *p = reinterpret_cast<u32x2 *>(lds + dst[r]);
+                if (where[r] >= 0) {
+                    u32x2 *p = reinterpret_cast<u32x2 *>(lds + where[r]);
                     p[0] = u32x2{val[r].x, val[r].y};
                     p[1] = u32x2{val[r].z, val[r].w};
                 }
@@ -316,11 +339,14 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
     // 16-byte stores (2-byte stores, one per lane and position, are what limits this kernel
     // otherwise): for one xi the tiles of the group are adjacent in V, twb*64 contiguous bytes.
     if (active) {
-        T *mine = lds + j * kChanBlock + c_in;
         const int first = half == 0 ? 0 : SP * N, count = half == 0 ? SP * N : (N - SP) * N;
+        const int stride = sh.twb * kChanBlock;            // elements between consecutive xi
+        T *mine = lds + j * kChanBlock + c_in + first * stride;
 #pragma unroll
-        for (int e = 0; e < ROWS_MAX * N; ++e)
-            if (e < count) mine[(first + e) * sh.twb * kChanBlock] = res[e];
+        for (int e = 0; e < ROWS_MAX * N; ++e) {
+            if (e < count) *mine = res[e];
+            mine += stride;
+        }
     }
     __syncthreads();
     {
@@ -396,7 +422,9 @@ static int launch_it(const nova_transforms *t, const void *x, void *V, const Geo
     constexpr int PE = 16 / (int)sizeof(T);
     InCoef<N> coef;
     fill_in_coef<N>(t, coef);
-    const bool vec = g.W % PE == 0 && ((uintptr_t)x % 16) == 0;
+    // (vector path: byte offsets inside one block of 32 channel planes are 32-bit)
+    const bool vec = g.W % PE == 0 && ((uintptr_t)x % 16) == 0 &&
+                     (long long)kChanBlock * g.H * g.W * (long long)sizeof(T) < (1LL << 31);
     // tiles per group: at most 8 (two waves per tile pair, 512 threads); the LDS block holds first
     // the strip, then the results [xi][tile][32], and may take at most 64 KiB
     StripShape sh;
@@ -427,6 +455,9 @@ static int launch_it(const nova_transforms *t, const void *x, void *V, const Geo
         sh.w_magic = (unsigned)((((unsigned long long)1 << 32) + g.W - 1) / g.W);
     }
     const int threads = ((sh.twb + 1) / 2) * 128;        // a pair of waves per pair of tiles
+    sh.step_q = threads % sh.pieces;
+    sh.step_a = (threads / sh.pieces) % sh.rows;
+    sh.step_c = threads / (sh.pieces * sh.rows);
     const long long blocks = (long long)sh.groups * ceil_div(g.tiles_h, trb) * g.c_blocks * g.N;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
     void (*kern)(const T *, T *, int, int, int, int, int, int, long long, long long, StripShape, InCoef<N>);
