@@ -147,6 +147,31 @@ def main():
                     frac=round(dom["gbs"] / HBM_PEAK_GBS, 4), traffic=traffic,
                     launch_us=round(dom["us"], 2), algorithmic_bytes=dom["bytes"])
 
+    # ---- the same K steps replayed from a HIP graph (10 steps per graph): what the step costs once the
+    # host-side launch work is taken out; reported beside the headline, never as `value`
+    graph_info = None
+    try:
+        per_graph = 10
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(per_graph):
+                step()
+        replays = max(1, args.steps // per_graph)
+        graph.replay()
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(replays):
+            graph.replay()
+        g1.record()
+        torch.cuda.synchronize()
+        g_ms = g0.elapsed_time(g1) / (replays * per_graph)
+        graph_info = dict(steps_per_graph=per_graph, ms_per_step=round(g_ms, 4),
+                          value=round(direct_flop / (g_ms * 1e-3) / 1e12, 2), unit="TFLOP/s")
+        del graph
+    except RuntimeError as exc:                        # capture refused: report, do not hide
+        graph_info = dict(error=str(exc)[:200])
+
     # ---- the same step with the products M kept in binary16 (half the M traffic, one more rounding):
     # reported beside the headline, never as `value`
     variant = None
@@ -223,6 +248,8 @@ def main():
         "stages": {k: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()}
                    for k, v in stages.items()},
     }
+    if graph_info is not None:
+        out["graph_replay"] = graph_info
     if variant is not None:
         out["variant_products_f16"] = variant
     out.update(result_extra)

@@ -603,3 +603,36 @@ def test_r5_fp32_against_definition(m, pset):
     assert err <= max(1e-5, 4 * own)
     if m == 2:
         assert rel_l2(got["y"], want) <= 1e-5 and np.abs(got["y"] - want).max() <= 1e-4
+
+
+def test_graph_capture_replays_match_eager():
+    # the conv call enqueues kernels only (no allocation, no memset, no synchronisation), so it can be
+    # captured in a graph; every replay, with eager work and synchronisation in between, must give
+    # what the eager call gives for the input that is in the buffer at that time
+    say("[case] graph capture of nova_winograd_conv2d")
+    points = synth.point_set("nova", 6)
+    t = nova.nova_make_transforms(points, 6, 3)
+    N, C, K, H, W = 3, 64, 64, 30, 36
+    rng = np.random.default_rng(77)
+    w = (rng.standard_normal((K, C, 3, 3)) * np.sqrt(2.0 / (9.0 * C))).astype(np.float16)
+    U = nova.nova_filter_transform(t, torch.from_numpy(w).to(DEV))
+    x = torch.zeros((N, C, H, W), dtype=torch.float16, device=DEV)
+    y = torch.empty((N, K, H, W), dtype=torch.float16, device=DEV)
+    ws = torch.empty(nova.nova_conv2d_workspace_bytes(N, C, H, W, K, 6, nova.NOVA_F16), dtype=torch.uint8, device=DEV)
+    nova.nova_winograd_conv2d(t, x, U, K, y=y, workspace=ws)           # warm up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        nova.nova_winograd_conv2d(t, x, U, K, y=y, workspace=ws, flags=nova.NOVA_FLAG_RELU)
+    for rep in range(4):
+        fresh = torch.from_numpy(rng.standard_normal((N, C, H, W)).astype(np.float16)).to(DEV)
+        x.copy_(fresh)
+        y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = y.clone()
+        want = nova.nova_winograd_conv2d(t, fresh, U, K, flags=nova.NOVA_FLAG_RELU)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), f"replay {rep} differs from the eager result"
+        assert torch.isfinite(got).all()
