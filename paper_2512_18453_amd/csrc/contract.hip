@@ -5,10 +5,13 @@
 // (rows x 32-channel) operand tile is one contiguous piece of memory and every lane's MFMA
 // fragment is a 16-byte read.
 //
-// binary16 path: v_mfma_f32_32x32x16_f16, binary32 accumulation.  A workgroup of 4 waves owns a
-// BM x BN tile of one M[xi]; the channel loop moves 32 channels per step through double-buffered
-// LDS (rows padded from 64 to 80 bytes, which spreads the 16 lanes of a 128-bit read phase over
-// all 64 banks), global loads for step s+1 are issued before the MFMAs of step s.
+// binary16 path: v_mfma_f32_32x32x16_f16, binary32 accumulation, two kernels.
+//   streaming kernel (C = 64, 128 or 256 and K a multiple of 64; further down): U stays in
+//     registers, V streams once through an LDS ring filled by direct global->LDS loads;
+//   tiled kernel (everything else): a workgroup of 4 waves owns a BM x BN tile of one M[xi]; the
+//     channel loop moves 32 channels per step through double-buffered LDS (rows padded from 64 to
+//     80 bytes, which spreads the 16 lanes of a 128-bit read phase over all 64 banks), global loads
+//     for step s+1 are issued before the MFMAs of step s.
 // binary32 path: same layouts, plain FMA tiles (validation path, not tuned).
 #include <type_traits>
 
@@ -32,7 +35,6 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
 
-constexpr bool kUseStreamKernel = true;
 constexpr int kRowHalves = 40;   // LDS row pitch of a 32-channel operand row, in binary16 units (80 B)
 
 template <int BM, int BN, int WM, int WN, typename MT>
@@ -483,7 +485,7 @@ static int launch_c16_shape(const void *U, const void *V, void *Mo, const Geomet
     // ring depth S: as many stages as fit about 128 KiB of LDS, at most 8
     const int cb = g.c_blocks;
     const int wn = g.Kp % 256 == 0 ? 4 : g.Kp % 128 == 0 ? 2 : g.Kp % 64 == 0 ? 1 : 0;
-    if (kUseStreamKernel) {
+    {
         //                                            WN WM NB CB  S OCC
         if (wn == 4 && cb == 8) return launch_stream<8, 1, 1, 8, 4, 2, MT>(U, V, Mo, g, s);   // 8 waves x 32 channels
         if (wn == 4 && cb == 4) return launch_stream<4, 1, 2, 4, 8, 2, MT>(U, V, Mo, g, s);

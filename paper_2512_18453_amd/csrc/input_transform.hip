@@ -3,13 +3,13 @@
 //
 // One workgroup takes one image, one tile row, a group of TWB neighbouring tiles and one block
 // of 32 channels (for narrow images, where a tile row has few tiles: TRB neighbouring tile rows
-// of full width).  The 32-channel x (TRB*m + r - 1 rows) x (TWB*m + r - 1 columns) input strip is staged in LDS
-// in the order it has in memory (16-byte pieces when W allows, all loads of a round in flight
-// together), with a channel pitch that puts the 32 channels of a half-wave into 32 different
-// banks for the per-thread tile reads (thread = one tile x one channel, 32 consecutive lanes =
-// 32 consecutive channels).  Each thread then transforms its tile in registers and writes n*n values,
-// 64 (fp16) or 128 (fp32) contiguous bytes per half-wave and position xi; the TWB tiles of the
-// group are adjacent in t, so a workgroup writes TWB*64 contiguous bytes per xi.
+// of full width).  The 32-channel x (TRB*m + r - 1 rows) x (TWB*m + r - 1 columns) input strip is
+// staged in LDS in the order it has in memory (16-byte pieces, all loads of a round in flight
+// together), with a channel pitch that keeps the per-thread window reads free of bank conflicts.
+// Thread = one tile x one channel (32 consecutive lanes = 32 consecutive channels); a pair of waves
+// shares two tiles and splits the rows of the transform between them.  The n*n results of a tile
+// go back through LDS as [xi][tile][32 channels], so that they leave in 16-byte stores: the tiles
+// of a group are adjacent in t, so a workgroup writes TWB*64 (fp16) contiguous bytes per xi.
 //
 // Arithmetic contract (binary32): a 1D transform row is E + O, with E / O fused multiply-add
 // chains over the even / odd input indices in ascending order, columns of the tile first, then
