@@ -448,7 +448,9 @@ static int launch_it(const nova_transforms *t, const void *x, void *V, const Geo
     const size_t lds_bytes = lds_need(twb, trb);         // (leaves sh.groups alone)
     if (lds_bytes > 64 * 1024 || sh.pieces < 2) return (int)hipErrorInvalidValue;
     // narrow images whose width is not a whole number of pieces: flat staging
-    const bool flat = !vec && sh.groups == 1 && ((uintptr_t)x % 16) == 0 && (long long)sh.rows * g.W < (1 << 15);
+    // (W >= 2: the reciprocal used for divisions by W does not exist for 1; such images take the scalar path)
+    const bool flat = !vec && sh.groups == 1 && ((uintptr_t)x % 16) == 0 && g.W >= 2 &&
+                      (long long)sh.rows * g.W < (1 << 15);
     if (flat) {
         sh.pieces = (sh.rows * g.W + 2 * (PE - 1)) / PE;    // pieces that can touch a run of rows*W elements
         sh.piece_magic = (unsigned)((((unsigned long long)1 << 32) + sh.pieces - 1) / sh.pieces);

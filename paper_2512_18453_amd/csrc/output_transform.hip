@@ -258,7 +258,9 @@ static int launch_ot(const nova_transforms *t, const void *Mp, void *y, const Ge
     if ((size_t)g.k_blocks * g.Tp * kChanBlock * sizeof(MT) >= ((size_t)1 << 32)) return (int)hipErrorInvalidValue;
     const bool aligned = ((uintptr_t)y % 16) == 0;
     const bool vec = g.W % PE == 0 && aligned && (sh.groups == 1 || (twb * M) % PE == 0);
-    const bool flat = !vec && aligned && sh.groups == 1 && (long long)sh.rows * g.W < (1 << 15);
+    // (W >= 2 and at least two pieces: the reciprocals used for the divisions do not exist for 1)
+    const bool flat = !vec && aligned && sh.groups == 1 && g.W >= 2 && sh.rows * g.W + 2 * (PE - 1) >= 2 * PE &&
+                      (long long)sh.rows * g.W < (1 << 15);
     if (flat) {
         sh.pieces = (sh.rows * g.W + 2 * (PE - 1)) / PE;
         sh.piece_magic = (unsigned)((((unsigned long long)1 << 32) + sh.pieces - 1) / sh.pieces);

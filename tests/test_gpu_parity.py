@@ -636,3 +636,31 @@ def test_graph_capture_replays_match_eager():
         torch.cuda.synchronize()
         assert torch.equal(got, want), f"replay {rep} differs from the eager result"
         assert torch.isfinite(got).all()
+
+
+DEGENERATE = [(1, 1, 1, 1, 1), (1, 1, 1, 1, 37), (2, 3, 2, 40, 1), (1, 2, 2, 8, 8), (1, 33, 1, 16, 16),
+              (1, 1, 65, 5, 64), (1, 4, 4, 3, 130), (5, 2, 3, 2, 2)]
+
+
+@pytest.mark.parametrize("m,r", [(2, 3), (4, 3), (6, 3), (8, 3), (2, 5), (6, 5)])
+def test_degenerate_shapes(m, r):
+    # single pixels, single rows and columns, one channel, images smaller than a tile, rows wider than
+    # one group: every staging / store variant at its smallest and at its ragged edge
+    n_points = m + r - 2
+    points = synth.point_set("nova", n_points - 1) if n_points - 1 in (4, 6, 8) else synth.point_set("standard", n_points - 1)
+    t = nova.nova_make_transforms(points, m, r)
+    rng = np.random.default_rng(1000 + 10 * m + r)
+    for (N, C, K, H, W) in DEGENERATE:
+        for dtype, storage in ((np.float16, 16), (np.float32, 32)):
+            say(f"[case] degenerate F({m},{r}) {np.dtype(dtype).name} N={N} C={C} K={K} H={H} W={W}")
+            x = rng.standard_normal((N, C, H, W)).astype(dtype)
+            w = (rng.standard_normal((K, C, r, r)) * np.sqrt(2.0 / (r * r * C))).astype(dtype)
+            got = run_stages(t, x, w)
+            x64, w64 = x.astype(np.float64), w.astype(np.float64)
+            y_o, U_o, V_o, _ = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=storage,
+                                                            want_intermediates=True)
+            same(got["U"], U_o, "U")
+            same(got["V"], V_o, "V")
+            assert np.array_equal(got["y"], got["y_conv"])
+            scale = max(np.abs(y_o).max(), 1e-30)
+            assert np.abs(got["y"] - y_o).max() <= (4e-2 if storage == 16 else 1e-3) * scale
