@@ -664,3 +664,60 @@ def test_degenerate_shapes(m, r):
             assert np.array_equal(got["y"], got["y_conv"])
             scale = max(np.abs(y_o).max(), 1e-30)
             assert np.abs(got["y"] - y_o).max() <= (4e-2 if storage == 16 else 1e-3) * scale
+
+
+def test_random_shapes_sweep():
+    # a fixed pseudo-random sample of small layers over every supported (m, r), both storage formats,
+    # with and without ReLU / binary16 products: U and V bit for bit, y against the emulation
+    sweep_random_shapes(20251127, 70)
+    sweep_random_shapes(20251128, 30, max_hw=300, max_ch=9)          # wide / tall images: several tile groups
+
+
+def sweep_random_shapes(seed, count, max_hw=70, max_ch=70):
+    rng = np.random.default_rng(seed)
+    combos = [(2, 3), (4, 3), (6, 3), (8, 3), (2, 5), (4, 5), (6, 5)]
+    handles = {}
+    for case in range(count):
+        m, r = combos[case % len(combos)]
+        n_fin = m + r - 2
+        # integer points only where they are well conditioned (n <= 6); beyond that the summation order of
+        # the contraction decides more digits of y than any fixed tolerance allows
+        name = "standard" if n_fin - 1 == 2 or (n_fin - 1 == 4 and case % 3 == 0) else "nova"
+        points = synth.point_set(name, n_fin - 1)
+        key = (m, r, name)
+        if key not in handles:
+            handles[key] = nova.nova_make_transforms(points, m, r)
+        t = handles[key]
+        N, C, K = int(rng.integers(1, 4)), int(rng.integers(1, max_ch + 1)), int(rng.integers(1, max_ch + 1))
+        H, W = int(rng.integers(1, max_hw + 1)), int(rng.integers(1, max_hw + 1))
+        if case % 4 == 1:
+            W = (W + 7) // 8 * 8                                                        # 16-byte rows
+        if case % 10 == 0:
+            C, K = int(rng.choice([64, 128])), int(rng.choice([64, 128, 256]))          # streaming contraction
+        f16 = case % 4 != 3
+        flags = 0
+        if case % 5 == 1:
+            flags |= nova.NOVA_FLAG_RELU
+        if f16 and case % 7 == 2:
+            flags |= nova.NOVA_FLAG_M_F16
+        dtype = np.float16 if f16 else np.float32
+        say(f"[case] sweep {case}: F({m},{r}) {name} {np.dtype(dtype).name} N={N} C={C} K={K} H={H} W={W} flags={flags}")
+        x = rng.standard_normal((N, C, H, W)).astype(dtype)
+        w = (rng.standard_normal((K, C, r, r)) * np.sqrt(2.0 / (r * r * C))).astype(dtype)
+        got = run_stages(t, x, w, flags=flags)
+        x64, w64 = x.astype(np.float64), w.astype(np.float64)
+        y_o, U_o, V_o, _ = conv.winograd_conv2d_emulated(
+            x64, w64, pts(points), m, storage=16 if f16 else 32, relu=bool(flags & nova.NOVA_FLAG_RELU),
+            m_storage=16 if flags & nova.NOVA_FLAG_M_F16 else 32, want_intermediates=True)
+        same(got["U"], U_o, "U")
+        same(got["V"], V_o, "V")
+        assert np.array_equal(got["y"], got["y_conv"], equal_nan=True)
+        fin = np.isfinite(y_o)
+        assert (np.isfinite(got["y"]) == fin).mean() > 0.99
+        if fin.all() and np.isfinite(got["y"]).all():
+            want = conv.direct_conv2d(x64, w64)
+            own = rel_l2(y_o, np.maximum(want, 0.0) if flags & nova.NOVA_FLAG_RELU else want)
+            # binary32: the device accumulates the channel sum in binary32, the emulation in fp64; both
+            # carry the conditioning of the points, which `own` measures
+            tol = 5e-3 if f16 else max(1e-5, 8 * own)
+            assert rel_l2(got["y"], y_o) < tol, (rel_l2(got["y"], y_o), tol)
