@@ -212,7 +212,10 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
                     if (c_in < kChanBlock) where[r] = dst;
                     const bool ok = c_in < c_lim && (unsigned)(a - a_lo) < a_span && (unsigned)(q - q_lo) < q_span;
                     if (ok)
-                        val[r] = *reinterpret_cast<const NOVA_GLOBAL u32x4 *>(plane_element(blk, (unsigned)off * (unsigned)sizeof(T)));
+                        // x is not read again by this call: streaming hint, so that it does not push V and M
+                        // out of the last-level cache
+                        val[r] = __builtin_nontemporal_load(reinterpret_cast<const NOVA_GLOBAL u32x4 *>(
+                            plane_element(blk, (unsigned)off * (unsigned)sizeof(T))));
                     q += sh.step_q; a += sh.step_a; c_in += sh.step_c; dst += dst_step; off += off_step;
                     if (q >= sh.pieces) { q -= sh.pieces; ++a; dst += dst_wrap_q; off += off_wrap_q; }
                     if (a >= sh.rows) { a -= sh.rows; ++c_in; dst += dst_wrap_a; off += off_wrap_a; }

@@ -107,7 +107,14 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
         for (int b = 0; b < N; ++b) {
             float v[N], o[M];
 #pragma unroll
-            for (int a = 0; a < N; ++a) v[a] = (float)*plane_element(Mp + (size_t)(a * N + b) * xi_stride, in_plane);
+            for (int a = 0; a < N; ++a) {
+                const NOVA_GLOBAL MT *src = plane_element(Mp + (size_t)(a * N + b) * xi_stride, in_plane);
+                // last use of M.  In binary32 it is the largest tensor of the call and is read with the
+                // streaming hint, so that it leaves the last-level cache behind it; in binary16 the
+                // hint measured slower (its lines are better left to be overwritten in the cache)
+                if constexpr (sizeof(MT) == 4) v[a] = (float)__builtin_nontemporal_load(src);
+                else v[a] = (float)*src;
+            }
             output_transform_1d<N, R, SYM>(v, o, coef);
 #pragma unroll
             for (int p = 0; p < M; ++p) z[p][b] = o[p];
@@ -144,8 +151,8 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
             if (k >= K || h >= H) continue;
             const u32x2 *in = reinterpret_cast<const u32x2 *>(lds + kk * sh.k_pitch + p * sh.cols_pitch + q * PE);
             const u32x2 lo = in[0], hi = in[1];
-            *reinterpret_cast<u32x4 *>(y + (((size_t)img * K + k) * H + h) * W + w0 + q * PE) =
-                u32x4{lo.x, lo.y, hi.x, hi.y};
+            u32x4 *dst = reinterpret_cast<u32x4 *>(y + (((size_t)img * K + k) * H + h) * W + w0 + q * PE);
+            __builtin_nontemporal_store(u32x4{lo.x, lo.y, hi.x, hi.y}, dst);    // y is not read again by this call
         }
     } else if constexpr (STG == kStoreFlat) {
         // the group spans the width: rows h0 .. h1-1 of one channel are one run of y
@@ -180,7 +187,7 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
             if (rel >= 0 && rel + PE <= run) {
                 u32x4 piece;
                 __builtin_memcpy(&piece, val, 16);
-                *reinterpret_cast<u32x4 *>(y + p0) = piece;
+                __builtin_nontemporal_store(piece, reinterpret_cast<u32x4 *>(y + p0));
             } else {
 #pragma unroll
                 for (int e = 0; e < PE; ++e)
