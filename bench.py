@@ -39,13 +39,15 @@ MEASURED_TRAFFIC_BYTES = {
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="vgg_conv3_f83_fp16")
     ap.add_argument("--points", default="nova")
     ap.add_argument("--images-per-slab", type=int, default=0, help="0 = library default")
     ap.add_argument("--m-f16", action="store_true", help="keep the products M in fp16 (NOVA_FLAG_M_F16)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg (profiling runs)")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the graph-replay and binary16-products legs (profiling runs: one configuration per kernel)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy, the yardstick for rocprofv3's FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
@@ -151,6 +153,8 @@ def main():
     # host-side launch work is taken out; reported beside the headline, never as `value`
     graph_info = None
     try:
+        if args.headline_only:
+            raise StopIteration
         per_graph = 10
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
@@ -169,13 +173,15 @@ def main():
         graph_info = dict(steps_per_graph=per_graph, ms_per_step=round(g_ms, 4),
                           value=round(direct_flop / (g_ms * 1e-3) / 1e12, 2), unit="TFLOP/s")
         del graph
+    except StopIteration:
+        pass
     except RuntimeError as exc:                        # capture refused: report, do not hide
         graph_info = dict(error=str(exc)[:200])
 
     # ---- the same step with the products M kept in binary16 (half the M traffic, one more rounding):
     # reported beside the headline, never as `value`
     variant = None
-    if dt == nova.NOVA_F16 and not args.m_f16:
+    if dt == nova.NOVA_F16 and not args.m_f16 and not args.headline_only:
         vflags = flags | nova.NOVA_FLAG_M_F16
         ws2 = torch.empty(nova.nova_conv2d_workspace_bytes(N, C, H, W, K, m, dt, vflags, args.images_per_slab),
                           dtype=torch.uint8, device=dev)
