@@ -55,7 +55,11 @@ enum { NOVA_MATRIX_A = 0, NOVA_MATRIX_BT = 1, NOVA_MATRIX_G = 2 };
 /* flags of nova_winograd_conv2d / nova_output_transform / nova_contract */
 enum {
     NOVA_FLAG_RELU = 1,     /* y = max(y, 0) fused into the output transform (NaN stays NaN) */
-    NOVA_FLAG_M_F16 = 2     /* NOVA_F16 only: keep the products M in binary16 instead of binary32 */
+    NOVA_FLAG_M_F16 = 2,    /* NOVA_F16 only: keep the products M in binary16 instead of binary32 */
+    NOVA_FLAG_POOL2 = 4     /* 2 x 2, stride-2 max-pool fused into the output transform (after the optional
+                               ReLU): y is [N][K][H/2][W/2]; H and W must be even (NOVA_EINVAL otherwise);
+                               a NaN in a window makes that output NaN.  The step between the blocks of a
+                               VGG-style stack, without writing and re-reading the unpooled layer */
 };
 
 /* ------------------------------------------------------------------ transforms (host) */

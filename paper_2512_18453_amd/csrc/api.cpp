@@ -133,6 +133,7 @@ extern "C" int nova_output_transform(const nova_transforms *t, const void *M, si
 {
     if (int rc = check_handle(t)) return rc;
     if (!M || !y || !dims_ok(N, 1, H, W, K) || !dtype_ok(dtype)) return NOVA_EINVAL;
+    if ((flags & NOVA_FLAG_POOL2) && (H % 2 != 0 || W % 2 != 0)) return NOVA_EINVAL;
     const Geometry g = make_geometry(N, 1, H, W, K, t->m, t->r);
     if (M_bytes < m_bytes(g, dtype, flags)) return NOVA_ENOSPC;
     return hip_result(launch_output_transform(t, M, y, g, dtype, flags, stream));
@@ -145,6 +146,7 @@ extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, con
     if (int rc = check_handle(t)) return rc;
     if (!x || !U || !y || !workspace || !dims_ok(N, C, H, W, K) || !dtype_ok(dtype)) return NOVA_EINVAL;
     if (((uintptr_t)workspace & 255) != 0) return NOVA_EINVAL;
+    if ((flags & NOVA_FLAG_POOL2) && (H % 2 != 0 || W % 2 != 0)) return NOVA_EINVAL;
     const int m = t->m, r = t->r;
 
     // largest slab (whole images) whose V and M fit the workspace; slab_bytes grows with the count
@@ -171,7 +173,8 @@ extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, con
         const int nb = (N - n0 < imgs) ? N - n0 : (int)imgs;
         const Geometry g = make_geometry(nb, C, H, W, K, m, r);
         const char *xs = (const char *)x + (size_t)n0 * C * H * W * es;
-        char *ys = (char *)y + (size_t)n0 * K * H * W * es;
+        const size_t y_image = (flags & NOVA_FLAG_POOL2) ? (size_t)K * (H / 2) * (W / 2) : (size_t)K * H * W;
+        char *ys = (char *)y + (size_t)n0 * y_image * es;
         if (int err = launch_input_transform(t, xs, Vbuf, g, dtype, stream)) return hip_result(err);
         if (int err = launch_contract(t, U, Vbuf, Mbuf, g, dtype, flags, stream)) return hip_result(err);
         if (int err = launch_output_transform(t, Mbuf, ys, g, dtype, flags, stream)) return hip_result(err);

@@ -61,6 +61,8 @@ struct OutShape {
     int k_pitch;      // LDS elements per channel
     int pieces;       // flat stores: 16-byte pieces that can touch one channel's run of rows * W elements
     unsigned piece_magic, w_magic, rows_magic;     // ceil(2^32 / d) for d = pieces, W, rows
+    int pool;         // 1: 2 x 2 max-pool while storing (H, W even)
+    unsigned half_rows_magic;                      // ceil(2^32 / (rows / 2)), rows / 2 >= 2
 };
 
 // How the block leaves LDS.
@@ -138,6 +140,30 @@ output_transform_kernel(const MT *__restrict__ Mp, T *__restrict__ y, int K, int
     const int w0 = tc0 * M;
     int cols = (sh.trb > 1 ? tiles_w : sh.twb) * M;
     if (w0 + cols > W) cols = W - w0;
+    if (sh.pool) {
+        // 2 x 2 max-pool on the way out: rows, columns, H, W, tr*M and w0 are all even, so no window
+        // straddles two groups.  One output element per thread and round, lanes along the pooled row.
+        const int Hp = H / 2, Wp = W / 2, pcols = cols / 2, prows = sh.rows / 2;
+        const unsigned pc_magic = (unsigned)((((unsigned long long)1 << 32) + pcols - 1) / pcols);
+        const int slots = kChanBlock * prows * pcols;
+        for (int s = threadIdx.x; s < slots; s += (int)blockDim.x) {
+            const int line = pcols > 1 ? (int)__umulhi((unsigned)s, pc_magic) : s;
+            const int qq = s - line * pcols;
+            const int kk = prows > 1 ? (int)__umulhi((unsigned)line, sh.half_rows_magic) : line;
+            const int pp = line - kk * prows;
+            const int k = kb * kChanBlock + kk, hp = (tr * M) / 2 + pp;
+            if (k >= K || hp >= Hp) continue;
+            const T *win = lds + kk * sh.k_pitch + 2 * pp * sh.cols_pitch + 2 * qq;
+            const float a = load_f32(win), b = load_f32(win + 1);
+            const float c = load_f32(win + sh.cols_pitch), d = load_f32(win + sh.cols_pitch + 1);
+            float best = a;                                   // a NaN in the window wins
+            best = (b > best || b != b) ? b : best;
+            best = (c > best || c != c) ? c : best;
+            best = (d > best || d != d) ? d : best;
+            store_from_f32(y + (((size_t)img * K + k) * Hp + hp) * Wp + w0 / 2 + qq, best);
+        }
+        return;
+    }
     if constexpr (STG == kStoreVec) {
         // W, w0 and cols are multiples of PE and y is 16-byte aligned
         const int pieces = cols / PE;
@@ -234,6 +260,8 @@ static size_t out_shape(int twb, int trb, OutShape &sh)
     if ((kp / 4) % 2 == 0) kp += 4;
     sh.k_pitch = kp;
     sh.pieces = 1; sh.piece_magic = 0; sh.w_magic = 0;
+    sh.pool = 0;
+    sh.half_rows_magic = sh.rows / 2 > 1 ? (unsigned)((((unsigned long long)1 << 32) + sh.rows / 2 - 1) / (sh.rows / 2)) : 0;
     return (size_t)kChanBlock * kp * sizeof(T);
 }
 
@@ -273,6 +301,7 @@ static int launch_ot(const nova_transforms *t, const void *Mp, void *y, const Ge
         sh.piece_magic = (unsigned)((((unsigned long long)1 << 32) + sh.pieces - 1) / sh.pieces);
         sh.w_magic = (unsigned)((((unsigned long long)1 << 32) + g.W - 1) / g.W);
     }
+    sh.pool = (flags & NOVA_FLAG_POOL2) ? 1 : 0;
     const int threads = ((sh.twb * 32 + 63) / 64) * 64;
     const long long blocks = (long long)sh.groups * ceil_div(g.tiles_h, trb) * g.k_blocks * g.N;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;

@@ -15,7 +15,7 @@ NOVA_F32, NOVA_F16 = 0, 1
 NOVA_MATRIX_A, NOVA_MATRIX_BT, NOVA_MATRIX_G = 0, 1, 2
 NOVA_ROWS_PLAIN, NOVA_ROWS_BALANCED, NOVA_ROWS_GIVEN = 0, 1, 2
 NOVA_MATRIX_F32, NOVA_MATRIX_F16, NOVA_MATRIX_INT8 = 0, 1, 2
-NOVA_FLAG_RELU, NOVA_FLAG_M_F16 = 1, 2
+NOVA_FLAG_RELU, NOVA_FLAG_M_F16, NOVA_FLAG_POOL2 = 1, 2, 4
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnova.so")
 _lib = None
@@ -256,7 +256,8 @@ def nova_winograd_conv2d(t, x, U, K, y=None, flags=0, workspace=None, images_per
     N, C, H, W = x.shape
     dt = _dtype_code(x)
     if y is None:
-        y = torch.empty((N, K, H, W), dtype=x.dtype, device=x.device)
+        out_hw = (H // 2, W // 2) if flags & NOVA_FLAG_POOL2 else (H, W)
+        y = torch.empty((N, K) + out_hw, dtype=x.dtype, device=x.device)
     if workspace is None:
         workspace = torch.empty(nova_conv2d_workspace_bytes(N, C, H, W, K, t.m, dt, flags, images_per_slab, t.r),
                                 dtype=torch.uint8, device=x.device)
@@ -290,7 +291,8 @@ def nova_output_transform(t, M, N, K, H, W, dtype, flags=0, y=None):
     """dtype: torch dtype of y (the storage format of the layer)."""
     dt = NOVA_F16 if dtype == torch.float16 else NOVA_F32
     if y is None:
-        y = torch.empty((N, K, H, W), dtype=dtype, device=M.device)
+        out_hw = (H // 2, W // 2) if flags & NOVA_FLAG_POOL2 else (H, W)
+        y = torch.empty((N, K) + out_hw, dtype=dtype, device=M.device)
     _check(lib().nova_output_transform(t.handle, _dev(M), M.numel() * M.element_size(), _dev(y), N, K, H, W, dt,
                                        flags, _stream()), "nova_output_transform")
     return y

@@ -721,3 +721,44 @@ def sweep_random_shapes(seed, count, max_hw=70, max_ch=70):
             # carry the conditioning of the points, which `own` measures
             tol = 5e-3 if f16 else max(1e-5, 8 * own)
             assert rel_l2(got["y"], y_o) < tol, (rel_l2(got["y"], y_o), tol)
+
+
+POOL_CASES = [(8, 2, 40, 36, 24, 32), (8, 1, 33, 20, 14, 14), (4, 2, 16, 16, 12, 260), (2, 1, 8, 8, 6, 10),
+              (6, 2, 24, 40, 18, 30), (8, 3, 64, 64, 56, 56), (6, 1, 5, 3, 2, 2), (4, 1, 7, 9, 22, 6)]
+
+
+@pytest.mark.parametrize("m,N,C,K,H,W", POOL_CASES)
+def test_fused_maxpool_equals_pooling_the_unfused_output(m, N, C, K, H, W):
+    # rounding to the storage format is monotonic, so pooling before or after the final rounding gives
+    # the same numbers: the fused result must equal the pooled unfused result bit for bit
+    points = synth.point_set("nova", m) if m > 2 else synth.point_set("standard", 2)
+    t = nova.nova_make_transforms(points, m, 3)
+    rng = np.random.default_rng(300 + m + W)
+    for dtype in (np.float16, np.float32):
+        say(f"[case] fused 2x2 max-pool F({m},3) {np.dtype(dtype).name} N={N} C={C} K={K} H={H} W={W}")
+        x = torch.from_numpy(rng.standard_normal((N, C, H, W)).astype(dtype)).to(DEV)
+        w = torch.from_numpy((rng.standard_normal((K, C, 3, 3)) * np.sqrt(2.0 / (9.0 * C))).astype(dtype)).to(DEV)
+        U = nova.nova_filter_transform(t, w)
+        for relu in (0, nova.NOVA_FLAG_RELU):
+            plain = nova.nova_winograd_conv2d(t, x, U, K, flags=relu)
+            fused = nova.nova_winograd_conv2d(t, x, U, K, flags=relu | nova.NOVA_FLAG_POOL2)
+            fused_slabs = nova.nova_winograd_conv2d(t, x, U, K, flags=relu | nova.NOVA_FLAG_POOL2, images_per_slab=1)
+            torch.cuda.synchronize()
+            assert fused.shape == (N, K, H // 2, W // 2)
+            want = torch.nn.functional.max_pool2d(plain.float(), 2).to(plain.dtype)
+            assert torch.equal(fused, want) and torch.equal(fused_slabs, want)
+            if relu:
+                assert torch.equal(fused, nova.nova_relu_maxpool2x2(plain))
+    # against the oracle, end to end
+    x64, w64 = x.cpu().numpy().astype(np.float64), w.cpu().numpy().astype(np.float64)
+    y_o = conv.relu_maxpool2x2(conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=32))
+    assert rel_l2(fused.cpu().numpy().astype(np.float64), y_o) < 1e-3
+
+
+def test_fused_maxpool_rejects_odd_sizes():
+    t = nova.nova_make_transforms(synth.point_set("nova", 4), 4, 3)
+    x = torch.zeros((1, 4, 7, 8), dtype=torch.float16, device=DEV)
+    U = nova.nova_filter_transform(t, torch.zeros((4, 4, 3, 3), dtype=torch.float16, device=DEV))
+    with pytest.raises(nova.NovaError) as err:
+        nova.nova_winograd_conv2d(t, x, U, 4, flags=nova.NOVA_FLAG_POOL2)
+    assert err.value.code == -1
