@@ -1,0 +1,92 @@
+#!/usr/bin/env python3
+"""The 13-layer VGG-16 3x3 convolution stack through libnova on one GPU: random He-normal weights,
+N(0,1) input, ReLU fused into every layer, 2x2 max-pool after layers 2, 4, 7, 10, 13 (fused into the
+output transform, or as the separate kernel with --separate-pool).  Prints one JSON line with the
+time of a forward pass and the per-layer times.
+
+    python -m paper_2512_18453_amd.vgg16_stack [--m 8] [--batch 32] [--points nova] [--separate-pool] [--m-f16]
+"""
+import argparse
+import json
+
+import torch
+
+from . import nova, synth
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--m", type=int, default=8, choices=(2, 4, 6, 8))
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--size", type=int, default=224)
+    ap.add_argument("--points", default="nova")
+    ap.add_argument("--separate-pool", action="store_true")
+    ap.add_argument("--m-f16", action="store_true", help="keep the products M in binary16")
+    ap.add_argument("--reps", type=int, default=10)
+    args = ap.parse_args()
+
+    dev = "cuda:0"
+    m, N = args.m, args.batch
+    t = nova.nova_make_transforms(synth.point_set(args.points, m), m, 3)
+    base = nova.NOVA_FLAG_RELU | (nova.NOVA_FLAG_M_F16 if args.m_f16 else 0)
+    gen = torch.Generator(device=dev).manual_seed(16)
+    x0 = torch.randn((N, 3, args.size, args.size), device=dev, generator=gen).half()
+    layers, H, ws_bytes = [], args.size, 0
+    for idx, (cin, cout) in enumerate(synth.VGG16_LAYERS, start=1):
+        w = (torch.randn((cout, cin, 3, 3), device=dev, generator=gen) * (2.0 / (9.0 * cin)) ** 0.5).half()
+        pool = idx in synth.VGG16_POOL_AFTER
+        full = torch.empty((N, cout, H, H), dtype=torch.float16, device=dev) if (not pool or args.separate_pool) else None
+        pooled = torch.empty((N, cout, H // 2, H // 2), dtype=torch.float16, device=dev) if pool else None
+        ws_bytes = max(ws_bytes, nova.nova_conv2d_workspace_bytes(N, cin, H, H, cout, m, nova.NOVA_F16, base))
+        layers.append(dict(U=nova.nova_filter_transform(t, w), cout=cout, H=H, pool=pool, full=full, pooled=pooled,
+                           flop=2.0 * N * cout * cin * H * H * 9))
+        if pool:
+            H //= 2
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def forward(events=None):
+        a = x0
+        for i, L in enumerate(layers):
+            if events is not None:
+                events[i].record()
+            if L["pool"] and not args.separate_pool:
+                a = nova.nova_winograd_conv2d(t, a, L["U"], L["cout"], y=L["pooled"], flags=base | nova.NOVA_FLAG_POOL2,
+                                              workspace=ws)
+            else:
+                a = nova.nova_winograd_conv2d(t, a, L["U"], L["cout"], y=L["full"], flags=base, workspace=ws)
+                if L["pool"]:
+                    a = nova.nova_relu_maxpool2x2(a, out=L["pooled"])
+        if events is not None:
+            events[len(layers)].record()
+        return a
+
+    for _ in range(3):
+        forward()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.reps):
+        forward()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.reps
+    per_layer = [0.0] * len(layers)
+    for _ in range(args.reps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(layers) + 1)]
+        out = forward(ev)
+        torch.cuda.synchronize()
+        for i in range(len(layers)):
+            per_layer[i] += ev[i].elapsed_time(ev[i + 1]) / args.reps
+    flop = sum(L["flop"] for L in layers)
+    print(json.dumps({
+        "workload": f"VGG-16 conv stack, batch {N}, {args.size}x{args.size}, F({m},3), {args.points} points, fp16",
+        "pooling": "separate kernel" if args.separate_pool else "fused (NOVA_FLAG_POOL2)",
+        "products_dtype": "f16" if args.m_f16 else "f32",
+        "ms_per_forward": round(ms, 4), "effective_tflops": round(flop / (ms * 1e-3) / 1e12, 1),
+        "finite_output": bool(torch.isfinite(out).all().item()),
+        "layer_us": [round(v * 1e3, 1) for v in per_layer],
+    }))
+
+
+if __name__ == "__main__":
+    main()
