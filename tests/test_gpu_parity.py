@@ -712,6 +712,12 @@ def sweep_random_shapes(seed, count, max_hw=70, max_ch=70):
         same(got["U"], U_o, "U")
         same(got["V"], V_o, "V")
         assert np.array_equal(got["y"], got["y_conv"], equal_nan=True)
+        if H % 2 == 0 and W % 2 == 0 and case % 2 == 0:
+            # pooling fused into the store phase against pooling the unfused result
+            xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+            pooled = nova.nova_winograd_conv2d(t, xd, nova.nova_filter_transform(t, wd), K, flags=flags | nova.NOVA_FLAG_POOL2)
+            ref = torch.nn.functional.max_pool2d(torch.from_numpy(got["y"]).to(DEV).float(), 2)
+            assert torch.equal(pooled.float().nan_to_num(nan=-7.0), ref.nan_to_num(nan=-7.0))
         fin = np.isfinite(y_o)
         assert (np.isfinite(got["y"]) == fin).mean() > 0.99
         if fin.all() and np.isfinite(got["y"]).all():
