@@ -8,7 +8,7 @@
 // together), with a channel pitch that keeps the per-thread window reads free of bank conflicts.
 // Thread = one tile x one channel (32 consecutive lanes = 32 consecutive channels); a pair of waves
 // shares two tiles and splits the rows of the transform between them.  The n*n results of a tile
-// go back through LDS as [xi][tile][32 channels], so that they leave in 16-byte stores: the tiles
+// go back through LDS as [tile][xi][32 channels], so that they leave in 16-byte stores: the tiles
 // of a group are adjacent in t, so a workgroup writes TWB*64 (fp16) contiguous bytes per xi.
 //
 // Arithmetic contract (binary32): a 1D transform row is E + O, with E / O fused multiply-add
@@ -84,7 +84,8 @@ struct StripShape {
     int ch_pitch;    // elements
     unsigned piece_magic;   // ceil(2^32 / pieces): s / pieces == mulhi(s, magic) while s * pieces < 2^32
     unsigned w_magic;       // the same for W (flat staging)
-    int step_q, step_a, step_c;   // the workgroup size B as digits: B = (step_c * rows + step_a) * pieces + step_q
+    int cs, passes, iters;  // vector staging: channels per chunk of a wave, passes of 64 lanes per chunk, chunks per wave
+    unsigned slot_magic;    // ceil(2^32 / (rows * pieces))
 };
 
 // How the strip gets into LDS.
@@ -179,55 +180,80 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
         // W is a multiple of PE and x is 16-byte aligned: every piece is wholly inside or outside
         // the image.  All loads of a round are issued before the first LDS write waits on them.
         w_al = (w_lo + PE) / PE * PE - PE;        // floor to a multiple of PE (w_lo >= -PAD >= -PE)
-        // Slot s = (c_in * rows + a) * pieces + q.  A thread takes s = tid, tid + B, tid + 2B, ..
-        // (B = workgroup size): its digits (c_in, a, q) are decoded once and then advanced by the
-        // digits of B (sh.step_*) with carries, and the LDS position and the offset in x move along
-        // with them: a few additions per piece instead of divisions and multiplications.
-        int line = (int)__umulhi(threadIdx.x, sh.piece_magic);
-        int q = (int)threadIdx.x - line * sh.pieces;
-        int c_in = (int)__umulhi((unsigned)line, sh.rows_magic), a = line - c_in * sh.rows;
-        // what of the strip lies inside the image: rows a_lo .. a_hi-1, pieces q_lo .. q_hi-1, channels < c_lim
+        // A wave takes sh.cs whole channels at a time (1 unless the strip of one channel has fewer
+        // than 64 pieces) and its lanes run over their (channel, row, piece) slots in sh.passes passes
+        // of 64.  What a lane does in one pass -- its offset in the channel plane, its place in LDS,
+        // whether the piece lies inside the image -- is decoded once and holds for every chunk of
+        // channels the wave visits; a chunk only moves the (scalar) plane base and the LDS base.
         const int a_lo = h_lo < 0 ? -h_lo : 0, a_hi = H - h_lo < sh.rows ? H - h_lo : sh.rows;
         const int q_lo = w_al < 0 ? (-w_al) / PE : 0, q_hi = (W - w_al) / PE < sh.pieces ? (W - w_al) / PE : sh.pieces;
         const int c_lim = C - cb * kChanBlock < kChanBlock ? C - cb * kChanBlock : kChanBlock;
         const unsigned a_span = (unsigned)(a_hi - a_lo), q_span = (unsigned)(q_hi - q_lo);
-        // uniform base of this channel block's first plane + 32-bit element offset (the launcher checks the range)
         const T *blk = x + ((size_t)img * C + (size_t)cb * kChanBlock) * H * W;
         const int HW = H * W;
-        int dst = c_in * sh.ch_pitch + a * sh.row_pitch + q * PE;                 // LDS element
-        int off = c_in * HW + (h_lo + a) * W + w_al + q * PE;                     // element of blk (if inside)
-        const int dst_step = sh.step_c * sh.ch_pitch + sh.step_a * sh.row_pitch + sh.step_q * PE;
-        const int off_step = sh.step_c * HW + sh.step_a * W + sh.step_q * PE;
-        const int dst_wrap_q = sh.row_pitch - sh.pieces * PE, off_wrap_q = W - sh.pieces * PE;
-        const int dst_wrap_a = sh.ch_pitch - sh.rows * sh.row_pitch, off_wrap_a = HW - sh.rows * W;
-        constexpr int RT = 8;                      // usually the whole strip in one round trip
-        while (__builtin_amdgcn_readfirstlane(c_in) < kChanBlock) {       // lane 0 of a wave holds its lowest slot
-            u32x4 val[RT];
-            int where[RT];
+        const int slots = sh.rows * sh.pieces;                       // per channel
+        const int lane = (int)(threadIdx.x & 63);
+        const int wave_u = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+        const int n_waves = (int)(blockDim.x >> 6);
+        constexpr int PU = 2, IU = 4;              // passes x chunks whose loads are in flight together
+        for (int p0 = 0; p0 < sh.passes; p0 += PU) {
+            int dst[PU], room[PU];
+            unsigned src[PU];
+            bool slot[PU], inside[PU];
 #pragma unroll
-            for (int r = 0; r < RT; ++r) {
-                where[r] = -1;
-                val[r] = u32x4{0u, 0u, 0u, 0u};
-                if (__builtin_amdgcn_readfirstlane(c_in) < kChanBlock) {  // uniform: skip rounds past the strip
-                    if (c_in < kChanBlock) where[r] = dst;
-                    const bool ok = c_in < c_lim && (unsigned)(a - a_lo) < a_span && (unsigned)(q - q_lo) < q_span;
-                    if (ok)
-                        // x is not read again by this call: streaming hint, so that it does not push V and M
-                        // out of the last-level cache
-                        val[r] = __builtin_nontemporal_load(reinterpret_cast<const NOVA_GLOBAL u32x4 *>(
-                            plane_element(blk, (unsigned)off * (unsigned)sizeof(T))));
-                    q += sh.step_q; a += sh.step_a; c_in += sh.step_c; dst += dst_step; off += off_step;
-                    if (q >= sh.pieces) { q -= sh.pieces; ++a; dst += dst_wrap_q; off += off_wrap_q; }
-                    if (a >= sh.rows) { a -= sh.rows; ++c_in; dst += dst_wrap_a; off += off_wrap_a; }
+            for (int pp = 0; pp < PU; ++pp) {
+                const int s = lane + 64 * (p0 + pp);
+                const int c_sub = (int)__umulhi((unsigned)s, sh.slot_magic);
+                const int rem = s - c_sub * slots;
+                const int a = (int)__umulhi((unsigned)rem, sh.piece_magic), q = rem - a * sh.pieces;
+                slot[pp] = p0 + pp < sh.passes && c_sub < sh.cs;
+                room[pp] = c_lim - c_sub;                     // the chunk's first channel must stay below this
+                inside[pp] = slot[pp] && (unsigned)(a - a_lo) < a_span && (unsigned)(q - q_lo) < q_span;
+                dst[pp] = c_sub * sh.ch_pitch + a * sh.row_pitch + q * PE;
+                src[pp] = (unsigned)(c_sub * HW + (h_lo + a) * W + w_al + q * PE) * (unsigned)sizeof(T);
+            }
+            // a lane outside the image never loads: its registers keep the zeros it writes to LDS
+            u32x4 val[IU][PU];
+#pragma unroll
+            for (int u = 0; u < IU; ++u)
+#pragma unroll
+                for (int pp = 0; pp < PU; ++pp) val[u][pp] = u32x4{0u, 0u, 0u, 0u};
+            for (int it0 = 0; it0 < sh.iters; it0 += IU) {
+                if (c_lim < kChanBlock) {
+                    // ragged channel block: a lane may load for one chunk and not for the next
+#pragma unroll
+                    for (int u = 0; u < IU; ++u)
+#pragma unroll
+                        for (int pp = 0; pp < PU; ++pp) val[u][pp] = u32x4{0u, 0u, 0u, 0u};
+                }
+#pragma unroll
+                for (int u = 0; u < IU; ++u) {
+                    const int c0 = ((it0 + u) * n_waves + wave_u) * sh.cs;       // wave-uniform
+                    if (c0 < kChanBlock) {
+                        const T *plane = blk + (size_t)c0 * HW;
+#pragma unroll
+                        for (int pp = 0; pp < PU; ++pp)
+                            if (inside[pp] && c0 < room[pp])
+                                // x is not read again by this call: streaming hint, so that it does not
+                                // push V and M out of the last-level cache
+                                val[u][pp] = __builtin_nontemporal_load(
+                                    reinterpret_cast<const NOVA_GLOBAL u32x4 *>(plane_element(plane, src[pp])));
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < IU; ++u) {
+                    const int c0 = ((it0 + u) * n_waves + wave_u) * sh.cs;
+                    if (c0 < kChanBlock) {
+#pragma unroll
+                        for (int pp = 0; pp < PU; ++pp)
+                            if (slot[pp]) {
+                                u32x2 *p = reinterpret_cast<u32x2 *>(lds + c0 * sh.ch_pitch + dst[pp]);
+                                p[0] = u32x2{val[u][pp].x, val[u][pp].y};
+                                p[1] = u32x2{val[u][pp].z, val[u][pp].w};
+                            }
+                    }
                 }
             }
-#pragma unroll
-            for (int r = 0; r < RT; ++r)
-                if (where[r] >= 0) {
-                    u32x2 *p = reinterpret_cast<u32x2 *>(lds + where[r]);
-                    p[0] = u32x2{val[r].x, val[r].y};
-                    p[1] = u32x2{val[r].z, val[r].w};
-                }
         }
     } else if constexpr (STG == kStageFlat) {
         // The group spans the image width (tc0 = 0, w_lo = -PAD).  Rows h0..h1 of one channel are one
@@ -338,18 +364,19 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
     }
     __syncthreads();                          // the strip has been read; its LDS is reused below
 
-    // ... and go back through LDS as [xi][tile of the group][32 channels], so that they leave in
+    // ... and go back through LDS as [tile of the group][xi][32 channels], so that they leave in
     // 16-byte stores (2-byte stores, one per lane and position, are what limits this kernel
     // otherwise): for one xi the tiles of the group are adjacent in V, twb*64 contiguous bytes.
+    // A tile takes (N*N + 1) rows of 32 channels: the spare row shifts neighbouring tiles by a
+    // quarter (binary16) or half (binary32) of the banks, so that the 16-byte reads below, which
+    // run over tiles within one xi, do not collide.
+    constexpr int TS = (N * N + 1) * kChanBlock;              // elements per tile
     if (active) {
-        const int first = half == 0 ? 0 : SP * N, count = half == 0 ? SP * N : (N - SP) * N;
-        const int stride = sh.twb * kChanBlock;            // elements between consecutive xi
-        T *mine = lds + j * kChanBlock + c_in + first * stride;
+        const int count = half == 0 ? SP * N : (N - SP) * N;
+        T *mine = lds + j * TS + (half == 0 ? 0 : SP * N * kChanBlock) + c_in;
 #pragma unroll
-        for (int e = 0; e < ROWS_MAX * N; ++e) {
-            if (e < count) *mine = res[e];
-            mine += stride;
-        }
+        for (int e = 0; e < ROWS_MAX * N; ++e)
+            if (e < count) mine[e * kChanBlock] = res[e];
     }
     __syncthreads();
     {
@@ -364,11 +391,26 @@ input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H,
         const size_t in_plane = ((size_t)cb * Ttot + t0) * kChanBlock;
         const size_t xi_stride = (size_t)c_blocks * Ttot * kChanBlock;
         const int n_waves = (int)blockDim.x >> 6;
-        for (int xi = wave; xi < N * N; xi += n_waves) {
-            T *plane = V + (size_t)xi * xi_stride + in_plane;
-            const T *rows = lds + xi * sh.twb * kChanBlock;
-            for (int l = lane; l < valid * PPR; l += 64)
-                *reinterpret_cast<u32x4 *>(plane + l * PE) = *reinterpret_cast<const u32x4 *>(rows + l * PE);
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+        // a lane moves the same piece of every xi: piece lane of the valid * PPR <= 64 that one xi has
+        const bool on = lane < valid * PPR;
+        const T *src = lds + (lane / PPR) * TS + (lane % PPR) * PE;
+        constexpr int UN = 4;                               // LDS reads in flight before the stores
+        for (int xi0 = wave_u; xi0 < N * N; xi0 += UN * n_waves) {
+            u32x4 piece[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int xi = xi0 + u * n_waves;
+                if (xi < N * N && on) piece[u] = *reinterpret_cast<const u32x4 *>(src + xi * kChanBlock);
+            }
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int xi = xi0 + u * n_waves;
+                if (xi < N * N && on) {
+                    T *plane = V + (size_t)xi * xi_stride + in_plane;
+                    *reinterpret_cast<NOVA_GLOBAL u32x4 *>(plane_element(plane, (unsigned)lane * 16u)) = piece[u];
+                }
+            }
         }
     }
 }
@@ -433,7 +475,7 @@ static int launch_it(const nova_transforms *t, const void *x, void *V, const Geo
     StripShape sh;
     auto lds_need = [&](int twb, int trb) {
         const size_t strip = strip_shape<N, R, T>(twb, trb, vec, sh);
-        const size_t out_stage = (size_t)N * N * twb * trb * kChanBlock * sizeof(T);
+        const size_t out_stage = (size_t)(N * N + 1) * twb * trb * kChanBlock * sizeof(T);
         return strip > out_stage ? strip : out_stage;
     };
     int twb_max = 8;
@@ -460,9 +502,14 @@ static int launch_it(const nova_transforms *t, const void *x, void *V, const Geo
         sh.w_magic = (unsigned)((((unsigned long long)1 << 32) + g.W - 1) / g.W);
     }
     const int threads = ((sh.twb + 1) / 2) * 128;        // a pair of waves per pair of tiles
-    sh.step_q = threads % sh.pieces;
-    sh.step_a = (threads / sh.pieces) % sh.rows;
-    sh.step_c = threads / (sh.pieces * sh.rows);
+    {
+        const int slots = sh.rows * sh.pieces;           // pieces of one channel's strip
+        sh.cs = 1;
+        while (sh.cs < kChanBlock && sh.cs * 2 * slots <= 64) sh.cs *= 2;
+        sh.passes = ceil_div(sh.cs * slots, 64);
+        sh.iters = ceil_div(kChanBlock, (threads / 64) * sh.cs);
+        sh.slot_magic = (unsigned)((((unsigned long long)1 << 32) + slots - 1) / slots);
+    }
     const long long blocks = (long long)sh.groups * ceil_div(g.tiles_h, trb) * g.c_blocks * g.N;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
     void (*kern)(const T *, T *, int, int, int, int, int, int, long long, long long, StripShape, InCoef<N>);
