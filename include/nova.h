@@ -192,6 +192,8 @@ int nova_filter_transform(const nova_transforms *t, const void *w, int K, int C,
  * that V and M of a slab stay cache resident; the slab size follows from the workspace it is
  * given.  images_per_slab = 0 asks for the library's default (as many images as fit 256 MiB of
  * V and M, at least one), N for the whole batch in one pass.  Returns 0 for invalid arguments.
+ * With C <= 4 (the first layer of an image network) the call keeps no M: the output transform forms
+ * the products itself, and the workspace holds V and a packed copy of the filters' first four channels.
  */
 size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K, int m, int r, int dtype, int flags,
                                    int images_per_slab);
@@ -200,6 +202,9 @@ size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K, int m, int
  * y = conv r x r (x, w), stride 1, zero border (r-1)/2 (3 x 3 with border 1 is the paper's case; the
  * 5 x 5 extension takes border 2, "same" output size), through F(m x m, r x r) with the handle's matrices:
  * input transform -> n*n channel contractions -> output transform, enqueued on `stream`.
+ * With C <= 4 the contraction is done inside the output transform, as a binary32 multiply-add chain
+ * over the channels (products of two stored values are exact in binary32), instead of on the matrix
+ * unit; the result agrees with nova_contract + nova_output_transform to rounding, not bit for bit.
  * x: device [N][C][H][W]; U: from nova_filter_transform with the same handle, K, C, dtype;
  * y: device [N][K][H][W]; all of dtype.  H, W >= 1 arbitrary: the image is zero-extended to
  * whole tiles and the result cropped.  workspace: device, at least

@@ -50,6 +50,14 @@ static size_t m_bytes(const Geometry &g, int dtype, int flags)
     return (size_t)g.n * g.n * g.k_blocks * (size_t)g.Tp * kChanBlock * es;
 }
 
+// What follows V in the workspace of nova_winograd_conv2d: the products M, or, with so few input
+// channels that the output transform forms the products itself, the packed filters.
+static bool few_channels(int C) { return C <= few_channels_limit(); }
+static size_t second_part_bytes(const Geometry &g, int dtype, int flags)
+{
+    return few_channels(g.C) ? few_channels_filter_bytes(g, dtype) : m_bytes(g, dtype, flags);
+}
+
 // V and M of a slab together: the size of the last-level cache (256 MB), so that what one stage
 // writes is still there when the next reads it.  Measured on 224 x 224 and 112 x 112 VGG layers
 // (batch 32): 7-10 % faster than the whole batch in one pass, and faster than smaller slabs.
@@ -85,7 +93,7 @@ extern "C" size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K,
     if (!dims_ok(N, C, H, W, K) || !device_tile_ok(m, r) || !dtype_ok(dtype) || images_per_slab < 0) return 0;
     auto slab_bytes = [&](long long count) {
         const Geometry sg = make_geometry((int)count, C, H, W, K, m, r);
-        return align256(v_bytes(sg, dtype)) + align256(m_bytes(sg, dtype, flags));
+        return align256(v_bytes(sg, dtype)) + align256(second_part_bytes(sg, dtype, flags));
     };
     long long imgs = images_per_slab;
     if (imgs == 0) {                             // as many images as fit the default budget
@@ -154,7 +162,7 @@ extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, con
         const Geometry sg = make_geometry((int)count, C, H, W, K, m, r);
         const size_t vb = align256(v_bytes(sg, dtype));
         if (v_part) *v_part = vb;
-        return vb + align256(m_bytes(sg, dtype, flags));
+        return vb + align256(second_part_bytes(sg, dtype, flags));
     };
     if (slab_bytes(1, nullptr) > workspace_bytes) return NOVA_ENOSPC;
     long long lo = 1, hi = N;                    // invariant: lo fits
@@ -169,6 +177,9 @@ extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, con
     const size_t es = dtype_size(dtype);
     char *Vbuf = (char *)workspace;
     char *Mbuf = Vbuf + v_part;
+    const bool few = few_channels(C);
+    if (few)
+        if (int err = launch_pack_few_channels(U, Mbuf, make_geometry(1, C, H, W, K, m, r), dtype, stream)) return hip_result(err);
     for (int n0 = 0; n0 < N; n0 += (int)imgs) {
         const int nb = (N - n0 < imgs) ? N - n0 : (int)imgs;
         const Geometry g = make_geometry(nb, C, H, W, K, m, r);
@@ -176,6 +187,10 @@ extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, con
         const size_t y_image = (flags & NOVA_FLAG_POOL2) ? (size_t)K * (H / 2) * (W / 2) : (size_t)K * H * W;
         char *ys = (char *)y + (size_t)n0 * y_image * es;
         if (int err = launch_input_transform(t, xs, Vbuf, g, dtype, stream)) return hip_result(err);
+        if (few) {
+            if (int err = launch_output_transform_few(t, Vbuf, Mbuf, ys, g, dtype, flags, stream)) return hip_result(err);
+            continue;
+        }
         if (int err = launch_contract(t, U, Vbuf, Mbuf, g, dtype, flags, stream)) return hip_result(err);
         if (int err = launch_output_transform(t, Mbuf, ys, g, dtype, flags, stream)) return hip_result(err);
     }

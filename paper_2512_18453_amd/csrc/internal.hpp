@@ -105,6 +105,14 @@ int launch_contract(const nova_transforms *t, const void *U, const void *V, void
                     const Geometry &g, int dtype, int flags, void *stream);
 int launch_output_transform(const nova_transforms *t, const void *M, void *y, const Geometry &g,
                             int dtype, int flags, void *stream);
+// Few input channels (C <= few_channels_limit()): the output transform forms the products itself
+// from V and a packed copy Uc of the filters' first channels (few_channels_filter_bytes), which
+// launch_pack_few_channels writes from U.
+int few_channels_limit();
+size_t few_channels_filter_bytes(const Geometry &g, int dtype);
+int launch_pack_few_channels(const void *U, void *Uc, const Geometry &g, int dtype, void *stream);
+int launch_output_transform_few(const nova_transforms *t, const void *V, const void *Uc, void *y,
+                                const Geometry &g, int dtype, int flags, void *stream);
 int launch_relu_maxpool2x2(const void *in, void *out, int N, int C, int H, int W, int dtype,
                            void *stream);
 }  // namespace nova
