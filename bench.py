@@ -27,9 +27,9 @@ MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA
 # profiles/vgg_conv3_f83_fp16_hbm_traffic.txt.  Keyed by (workload, points, products dtype,
 # images per slab, stage); anything not measured reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("vgg_conv3_f83_fp16", "nova", "f32", 32, "input_transform"): 134469178,
-    ("vgg_conv3_f83_fp16", "nova", "f32", 32, "contract"): 256241753,
-    ("vgg_conv3_f83_fp16", "nova", "f32", 32, "output_transform"): 212155197,
+    ("vgg_conv3_f83_fp16", "nova", "f32", 32, "input_transform"): 133487818,
+    ("vgg_conv3_f83_fp16", "nova", "f32", 32, "contract"): 256229368,
+    ("vgg_conv3_f83_fp16", "nova", "f32", 32, "output_transform"): 212141825,
     ("vgg_conv3_f83_fp16", "nova", "f16", 32, "input_transform"): 132316851,
     ("vgg_conv3_f83_fp16", "nova", "f16", 32, "contract"): 175330453,
     ("vgg_conv3_f83_fp16", "nova", "f16", 32, "output_transform"): 132427318,
