@@ -193,7 +193,8 @@ int nova_filter_transform(const nova_transforms *t, const void *w, int K, int C,
  * given.  images_per_slab = 0 asks for the library's default (as many images as fit 256 MiB of
  * V and M, at least one), N for the whole batch in one pass.  Returns 0 for invalid arguments.
  * With C <= 4 (the first layer of an image network) the call keeps no M: the output transform forms
- * the products itself, and the workspace holds V and a packed copy of the filters' first four channels.
+ * the products itself, and the workspace holds V in a compact 4-channel layout and a packed copy of the
+ * filters' first four channels.
  */
 size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K, int m, int r, int dtype, int flags,
                                    int images_per_slab);

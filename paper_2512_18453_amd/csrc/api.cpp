@@ -53,6 +53,10 @@ static size_t m_bytes(const Geometry &g, int dtype, int flags)
 // What follows V in the workspace of nova_winograd_conv2d: the products M, or, with so few input
 // channels that the output transform forms the products itself, the packed filters.
 static bool few_channels(int C) { return C <= few_channels_limit(); }
+static size_t first_part_bytes(const Geometry &g, int dtype)
+{
+    return few_channels(g.C) ? few_channels_input_bytes(g, dtype) : v_bytes(g, dtype);
+}
 static size_t second_part_bytes(const Geometry &g, int dtype, int flags)
 {
     return few_channels(g.C) ? few_channels_filter_bytes(g, dtype) : m_bytes(g, dtype, flags);
@@ -93,7 +97,7 @@ extern "C" size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K,
     if (!dims_ok(N, C, H, W, K) || !device_tile_ok(m, r) || !dtype_ok(dtype) || images_per_slab < 0) return 0;
     auto slab_bytes = [&](long long count) {
         const Geometry sg = make_geometry((int)count, C, H, W, K, m, r);
-        return align256(v_bytes(sg, dtype)) + align256(second_part_bytes(sg, dtype, flags));
+        return align256(first_part_bytes(sg, dtype)) + align256(second_part_bytes(sg, dtype, flags));
     };
     long long imgs = images_per_slab;
     if (imgs == 0) {                             // as many images as fit the default budget
@@ -160,7 +164,7 @@ extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, con
     // largest slab (whole images) whose V and M fit the workspace; slab_bytes grows with the count
     auto slab_bytes = [&](long long count, size_t *v_part) {
         const Geometry sg = make_geometry((int)count, C, H, W, K, m, r);
-        const size_t vb = align256(v_bytes(sg, dtype));
+        const size_t vb = align256(first_part_bytes(sg, dtype));
         if (v_part) *v_part = vb;
         return vb + align256(second_part_bytes(sg, dtype, flags));
     };
@@ -186,11 +190,12 @@ extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, con
         const char *xs = (const char *)x + (size_t)n0 * C * H * W * es;
         const size_t y_image = (flags & NOVA_FLAG_POOL2) ? (size_t)K * (H / 2) * (W / 2) : (size_t)K * H * W;
         char *ys = (char *)y + (size_t)n0 * y_image * es;
-        if (int err = launch_input_transform(t, xs, Vbuf, g, dtype, stream)) return hip_result(err);
         if (few) {
+            if (int err = launch_input_transform_few(t, xs, Vbuf, g, dtype, stream)) return hip_result(err);
             if (int err = launch_output_transform_few(t, Vbuf, Mbuf, ys, g, dtype, flags, stream)) return hip_result(err);
             continue;
         }
+        if (int err = launch_input_transform(t, xs, Vbuf, g, dtype, stream)) return hip_result(err);
         if (int err = launch_contract(t, U, Vbuf, Mbuf, g, dtype, flags, stream)) return hip_result(err);
         if (int err = launch_output_transform(t, Mbuf, ys, g, dtype, flags, stream)) return hip_result(err);
     }

@@ -547,4 +547,123 @@ int launch_input_transform(const nova_transforms *t, const void *x, void *V, con
     return (int)hipErrorInvalidValue;
 }
 
+// ---- Few input channels (C <= 4): V in the compact layout Vc [n*n][T][4] that the few-channel
+// output transform reads (no 32-channel blocks: 3 of 32 channels would carry data).  One pair of
+// waves takes 16 neighbouring tiles of a tile row and the 4 channels, lane = (tile, channel); the
+// two waves split the transform rows as above.  Same arithmetic contract; channels >= C are zero.
+constexpr int kFewIn = 4;                  // channels
+constexpr int kFewTiles = 64 / kFewIn;     // tiles per group
+
+template <int N, int R, typename T, bool SYM>
+__global__ void __launch_bounds__(128)
+input_transform_few_kernel(const T *__restrict__ x, T *__restrict__ Vc, int C, int H, int W,
+                           int tiles_h, int tiles_w, int groups, long long Ttot, int row_pitch, InCoef<N> coef)
+{
+    constexpr int M = N - R + 1;
+    constexpr int PAD = (R - 1) / 2;
+    constexpr int SP = RowSplit<N>::value;
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    T *lds = reinterpret_cast<T *>(lds_raw);
+
+    unsigned bid = blockIdx.x;
+    const int tg = bid % groups; bid /= groups;
+    const int tr = bid % tiles_h; bid /= tiles_h;
+    const int img = bid;
+    const int tc0 = tg * kFewTiles;
+    const int h_lo = tr * M - PAD, w_lo = tc0 * M - PAD;
+    const int cols = kFewTiles * M + R - 1;
+    const int ch_pitch = N * row_pitch;
+
+    // strip [4 channels][N rows][cols], lanes along W; outside the image and for channels >= C: zero
+    const unsigned cols_magic = (unsigned)((((unsigned long long)1 << 32) + cols - 1) / cols);
+    const int slots = kFewIn * N * cols;
+    constexpr int RT = 8;
+    for (int base = threadIdx.x; base < slots; base += RT * (int)blockDim.x) {
+        T val[RT];
+        int dst[RT];
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+            const int s = base + r * (int)blockDim.x;
+            const int line = (int)__umulhi((unsigned)s, cols_magic);       // (channel, row)
+            const int q = s - line * cols;
+            const int c = line / N, a = line - c * N;
+            const int h = h_lo + a, w = w_lo + q;
+            const bool ok = s < slots && c < C && h >= 0 && h < H && w >= 0 && w < W;
+            dst[r] = s < slots ? c * ch_pitch + a * row_pitch + q : -1;
+            val[r] = (T)0.0f;
+            if (ok) val[r] = x[(((size_t)img * C + c) * H + h) * W + w];
+        }
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+            if (dst[r] >= 0) lds[dst[r]] = val[r];
+    }
+    __syncthreads();
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int j = lane / kFewIn, c_in = lane % kFewIn;
+    if (tc0 + j >= tiles_w) return;
+    const T *tile = lds + c_in * ch_pitch + j * M;
+    constexpr int ROWS_MAX = SP > N - SP ? SP : N - SP;
+    T res[ROWS_MAX * N];
+    if (wave == 0) transform_rows_of_tile<N, T, SYM, false, 0, SP>(tile, row_pitch, res, 1, coef);
+    else           transform_rows_of_tile<N, T, SYM, false, SP, N>(tile, row_pitch, res, 1, coef);
+
+    // a wave writes 64 consecutive values (16 tiles x 4 channels) per xi
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int first = wave_u == 0 ? 0 : SP * N, count = wave_u == 0 ? SP * N : (N - SP) * N;
+    const long long t0 = ((long long)img * tiles_h + tr) * tiles_w + tc0;
+    const unsigned off = (unsigned)lane * (unsigned)sizeof(T);
+#pragma unroll
+    for (int e = 0; e < ROWS_MAX * N; ++e)
+        if (e < count) {
+            T *plane = Vc + ((size_t)(first + e) * Ttot + t0) * kFewIn;
+            *reinterpret_cast<NOVA_GLOBAL T *>(plane_element(plane, off)) = res[e];
+        }
+}
+
+template <int N, int R, typename T>
+static int launch_it_few(const nova_transforms *t, const void *x, void *Vc, const Geometry &g, hipStream_t stream)
+{
+    constexpr int M = N - R + 1;
+    if (g.C > kFewIn) return (int)hipErrorInvalidValue;
+    InCoef<N> coef;
+    fill_in_coef<N>(t, coef);
+    const int groups = ceil_div(g.tiles_w, kFewTiles);
+    const int row_pitch = (kFewTiles * M + R - 1 + 3) / 4 * 4;
+    const size_t lds_bytes = (size_t)kFewIn * N * row_pitch * sizeof(T);
+    const long long blocks = (long long)groups * g.tiles_h * g.N;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidValue;
+    auto kern = t->symmetric ? input_transform_few_kernel<N, R, T, true> : input_transform_few_kernel<N, R, T, false>;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(128), lds_bytes, stream,
+                       (const T *)x, (T *)Vc, g.C, g.H, g.W, g.tiles_h, g.tiles_w, groups, g.T, row_pitch, coef);
+    return (int)hipGetLastError();
+}
+
+size_t few_channels_input_bytes(const Geometry &g, int dtype)
+{
+    return (size_t)g.n * g.n * (size_t)g.T * kFewIn * dtype_size(dtype);
+}
+
+int launch_input_transform_few(const nova_transforms *t, const void *x, void *Vc, const Geometry &g,
+                               int dtype, void *stream)
+{
+    hipStream_t s = (hipStream_t)stream;
+    const bool h = dtype == NOVA_F16;
+    if (t->r == 3) {
+        switch (t->n) {
+        case 4: return h ? launch_it_few<4, 3, f16>(t, x, Vc, g, s) : launch_it_few<4, 3, float>(t, x, Vc, g, s);
+        case 6: return h ? launch_it_few<6, 3, f16>(t, x, Vc, g, s) : launch_it_few<6, 3, float>(t, x, Vc, g, s);
+        case 8: return h ? launch_it_few<8, 3, f16>(t, x, Vc, g, s) : launch_it_few<8, 3, float>(t, x, Vc, g, s);
+        case 10: return h ? launch_it_few<10, 3, f16>(t, x, Vc, g, s) : launch_it_few<10, 3, float>(t, x, Vc, g, s);
+        }
+    } else if (t->r == 5) {
+        switch (t->n) {
+        case 6: return h ? launch_it_few<6, 5, f16>(t, x, Vc, g, s) : launch_it_few<6, 5, float>(t, x, Vc, g, s);
+        case 8: return h ? launch_it_few<8, 5, f16>(t, x, Vc, g, s) : launch_it_few<8, 5, float>(t, x, Vc, g, s);
+        case 10: return h ? launch_it_few<10, 5, f16>(t, x, Vc, g, s) : launch_it_few<10, 5, float>(t, x, Vc, g, s);
+        }
+    }
+    return (int)hipErrorInvalidValue;
+}
+
 }  // namespace nova

@@ -110,6 +110,10 @@ int launch_output_transform(const nova_transforms *t, const void *M, void *y, co
 // launch_pack_few_channels writes from U.
 int few_channels_limit();
 size_t few_channels_filter_bytes(const Geometry &g, int dtype);
+// ... and reads V in the compact layout [n*n][T][4] that launch_input_transform_few writes
+size_t few_channels_input_bytes(const Geometry &g, int dtype);
+int launch_input_transform_few(const nova_transforms *t, const void *x, void *Vc, const Geometry &g,
+                               int dtype, void *stream);
 int launch_pack_few_channels(const void *U, void *Uc, const Geometry &g, int dtype, void *stream);
 int launch_output_transform_few(const nova_transforms *t, const void *V, const void *Uc, void *y,
                                 const Geometry &g, int dtype, int flags, void *stream);

@@ -13,7 +13,7 @@
 //
 // Few input channels (C <= 4, the first layer of an image network): the products are not read
 // from M but formed here, M[xi][t][k] = sum_c V[xi][t][c] U[xi][k][c] as a binary32 multiply-add
-// chain over c (the factors are exact in binary32), from V in its usual layout and a packed copy
+// chain over c (the factors are exact in binary32), from V in a compact layout Vc [n*n][T][4] and a packed copy
 // Uc [n*n][Kp][4] of the first four channels of U.  M, n*n*T*K values that would be written and
 // read once whatever C is, then never exists.
 #include <type_traits>
@@ -83,7 +83,7 @@ enum { kStoreScalar = 0, kStoreVec = 1, kStoreFlat = 2 };
 constexpr int kFewChannels = 4;
 
 // CF = 0: products read from Mp (MT: their type).  CF = kFewChannels: products formed from Vp
-// [n*n][1][Ttot][32] and Uc [n*n][k_blocks*32][CF]; MT = f16 rounds each product to binary16 first,
+// [n*n][Ttot][CF] and Uc [n*n][k_blocks*32][CF]; MT = f16 rounds each product to binary16 first,
 // as storing M in binary16 would.
 template <int N, int R, typename T, typename MT, bool SYM, int STG, bool RELU, int CF>
 __global__ void __launch_bounds__(512)
@@ -114,7 +114,6 @@ output_transform_kernel(const MT *__restrict__ Mp, const T *__restrict__ Vp, con
         typedef T few_t __attribute__((ext_vector_type(CF > 0 ? CF : 1)));
         few_t *Vs = reinterpret_cast<few_t *>(lds), *Us = Vs + N * N * sh.twb;
         const few_t *Vg = reinterpret_cast<const few_t *>(Vp), *Ug = reinterpret_cast<const few_t *>(Uc);
-        constexpr int RowV = kChanBlock / (CF > 0 ? CF : 1);        // few_t per 32-channel row of V
         for (int s = threadIdx.x; s < N * N * sh.twb; s += (int)blockDim.x) {
             const int xi = s / sh.twb, jj = s - xi * sh.twb;
             int sr = 0, sc = jj;
@@ -124,7 +123,7 @@ output_transform_kernel(const MT *__restrict__ Mp, const T *__restrict__ Vp, con
             for (int c = 0; c < CF; ++c) val[c] = (T)0.0f;
             if (tc0 + sc < tiles_w && tr + sr < tiles_h) {
                 const long long t = ((long long)img * tiles_h + tr + sr) * tiles_w + tc0 + sc;
-                val = Vg[((size_t)xi * Ttot + t) * RowV];
+                val = Vg[(size_t)xi * Ttot + t];
             }
             Vs[jj * (N * N) + xi] = val;
         }
@@ -411,7 +410,7 @@ static int launch_ot(const nova_transforms *t, const void *Mp, const void *few_u
     const size_t lds_bytes = lds_need(twb, trb);           // (leaves sh.groups alone)
     if (lds_bytes > 64 * 1024) return (int)hipErrorInvalidValue;
     if (CF == 0 && (size_t)g.k_blocks * g.Tp * kChanBlock * sizeof(MT) >= ((size_t)1 << 32)) return (int)hipErrorInvalidValue;
-    if (CF > 0 && ((size_t)g.T * kChanBlock * sizeof(T) >= ((size_t)1 << 32) || g.C > CF)) return (int)hipErrorInvalidValue;
+    if (CF > 0 && g.C > CF) return (int)hipErrorInvalidValue;
     const bool aligned = ((uintptr_t)y % 16) == 0;
     const bool vec = g.W % PE == 0 && aligned && (sh.groups == 1 || (twb * M) % PE == 0);
     // (W >= 2 and at least two pieces: the reciprocals used for the divisions do not exist for 1)
