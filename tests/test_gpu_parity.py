@@ -722,6 +722,7 @@ def test_random_shapes_sweep():
     # with and without ReLU / binary16 products: U and V bit for bit, y against the emulation
     sweep_random_shapes(20251127, 70)
     sweep_random_shapes(20251128, 30, max_hw=300, max_ch=9)          # wide / tall images: several tile groups
+    sweep_random_shapes(20251129, 30, max_hw=120, max_ch=4)          # first-layer path: at most 4 channels either way
 
 
 def sweep_random_shapes(seed, count, max_hw=70, max_ch=70):
