@@ -190,7 +190,7 @@ int nova_filter_transform(const nova_transforms *t, const void *w, int K, int C,
 /*
  * Workspace for nova_winograd_conv2d.  The call processes the batch in slabs of whole images so
  * that V and M of a slab stay cache resident; the slab size follows from the workspace it is
- * given.  images_per_slab = 0 asks for the library's default (as many images as fit 256 MiB of
+ * given (as many slabs as the largest size that fits would need, evened out: 16 + 16 images, not 20 + 12).  images_per_slab = 0 asks for the library's default (as many images as fit 256 MiB of
  * V and M, at least one), N for the whole batch in one pass.  Returns 0 for invalid arguments.
  * With C <= 4 (the first layer of an image network) the call keeps no M: the output transform forms
  * the products itself, and the workspace holds V in a compact 4-channel layout and a packed copy of the

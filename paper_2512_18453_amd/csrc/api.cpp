@@ -174,7 +174,9 @@ extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, con
         const long long mid = (lo + hi + 1) / 2;
         if (slab_bytes(mid, nullptr) <= workspace_bytes) lo = mid; else hi = mid - 1;
     }
-    const long long imgs = lo;
+    // (as many slabs as that size needs, but of equal size: 20 + 12 images run slower than 16 + 16)
+    const long long slab_count = (N + lo - 1) / lo;
+    const long long imgs = (N + slab_count - 1) / slab_count;
     size_t v_part = 0;
     (void)slab_bytes(imgs, &v_part);
 
