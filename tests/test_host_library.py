@@ -192,6 +192,12 @@ def test_sizes_follow_documented_layouts():
     assert one == 100 * 8 * 49 * 32 * 2 + 100 * 8 * 128 * 32 * 4
     default = nova.nova_conv2d_workspace_bytes(32, 256, 56, 56, 256, 8, nova.NOVA_F16, 0, 0)
     assert default == whole
+    # at most 4 input channels: V compact [n*n][T][4], packed filters [n*n][Kp][4], no M (each part 256-byte aligned)
+    few = nova.nova_conv2d_workspace_bytes(32, 3, 224, 224, 64, 8, nova.NOVA_F16, 0, 32)
+    assert few == 100 * (32 * 28 * 28) * 4 * 2 + 100 * 64 * 4 * 2
+    few32 = nova.nova_conv2d_workspace_bytes(2, 4, 9, 13, 40, 6, nova.NOVA_F32, 0, 2)                 # T = 12, Kp = 64
+    assert few32 == 64 * 12 * 4 * 4 + 64 * 64 * 4 * 4
+    assert nova.nova_conv2d_workspace_bytes(2, 5, 9, 13, 40, 6, nova.NOVA_F32, 0, 2) == 64 * 1 * 12 * 32 * 4 + 64 * 2 * 128 * 32 * 4
     # 5 x 5 kernels: n = m + 4, tiles still at stride m
     assert nova.nova_filter_bytes(64, 64, 4, nova.NOVA_F16, r=5) == 64 * 2 * 64 * 32 * 2
     assert nova.nova_input_bytes(2, 64, 9, 13, 6, nova.NOVA_F16, r=5) == 100 * 2 * 12 * 32 * 2       # T = 2*2*3
