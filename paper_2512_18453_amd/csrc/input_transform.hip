@@ -147,7 +147,7 @@ __device__ __forceinline__ void transform_rows_of_tile(const T *tile, int row_pi
 }
 
 template <int N, int R, typename T, bool SYM, int STG>
-__global__ void __launch_bounds__(512)
+__global__ void __launch_bounds__(N <= 8 ? 640 : 512)     // (n <= 8: groups of up to 10 tiles)
 input_transform_kernel(const T *__restrict__ x, T *__restrict__ V, int C, int H, int W,
                        int tiles_h, int tiles_w, int c_blocks, long long Ttot, long long x_elems,
                        StripShape sh, InCoef<N> coef)
@@ -470,7 +470,9 @@ static int launch_it(const nova_transforms *t, const void *x, void *V, const Geo
     // (vector path: byte offsets inside one block of 32 channel planes are 32-bit)
     const bool vec = g.W % PE == 0 && ((uintptr_t)x % 16) == 0 &&
                      (long long)kChanBlock * g.H * g.W * (long long)sizeof(T) < (1LL << 31);
-    // tiles per group: at most 8 (two waves per tile pair, 512 threads); the LDS block holds first
+    // tiles per group: at most 8 (two waves per tile pair, 512 threads); a row of 9 or 10 tiles (56 x 56 at
+    // m = 6) is taken whole for n <= 8 instead of split 5 + 5 (wider rows measured slower in groups of 10:
+    // 224 x 224 at m = 6, 234 against 174 us); the LDS block holds first
     // the strip, then the results [xi][tile][32], and may take at most 64 KiB
     StripShape sh;
     auto lds_need = [&](int twb, int trb) {
@@ -478,7 +480,8 @@ static int launch_it(const nova_transforms *t, const void *x, void *V, const Geo
         const size_t out_stage = (size_t)(N * N + 1) * twb * trb * kChanBlock * sizeof(T);
         return strip > out_stage ? strip : out_stage;
     };
-    int twb_max = 8;
+    // (binary16 only: the store loop moves one position's valid * 32 / PE <= 64 pieces in one step)
+    int twb_max = (N <= 8 && sizeof(T) == 2 && g.tiles_w > 8 && g.tiles_w <= 10) ? 10 : 8;
     while (twb_max > 1 && lds_need(twb_max, 1) > 64 * 1024) --twb_max;
     sh.groups = ceil_div(g.tiles_w, twb_max);
     const int twb = ceil_div(g.tiles_w, sh.groups);      // tiles of one tile row per group
@@ -486,6 +489,7 @@ static int launch_it(const nova_transforms *t, const void *x, void *V, const Geo
     int trb = 1;
     if (sh.groups == 1) {
         trb = 8 / twb;
+        if (trb < 1) trb = 1;
         if (trb > g.tiles_h) trb = g.tiles_h;
         while (trb > 1 && lds_need(twb, trb) > 64 * 1024) --trb;
     }

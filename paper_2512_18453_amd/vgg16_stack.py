@@ -5,6 +5,10 @@ output transform, or as the separate kernel with --separate-pool).  Prints one J
 time of a forward pass and the per-layer times.
 
     python -m paper_2512_18453_amd.vgg16_stack [--m 8] [--batch 32] [--points nova] [--separate-pool] [--m-f16]
+
+With --stages it times, layer by layer, the three stage entry points on the whole batch (no slabs, the
+products in binary32 or binary16 as chosen) and prints one line per layer: time and algorithmic
+bytes / time of the input transform (x + V), the contraction (U + V + M) and the output transform (M + y).
 """
 import argparse
 import json
@@ -12,6 +16,47 @@ import json
 import torch
 
 from . import nova, synth
+
+
+def stage_times(args):
+    dev = "cuda:0"
+    m, N, n = args.m, args.batch, args.m + 2
+    t = nova.nova_make_transforms(synth.point_set(args.points, m), m, 3)
+    flags = nova.NOVA_FLAG_RELU | (nova.NOVA_FLAG_M_F16 if args.m_f16 else 0)
+    m_es = 2 if args.m_f16 else 4
+    gen = torch.Generator(device=dev).manual_seed(16)
+    H = args.size
+    print(f"VGG-16 layers, batch {N}, F({m},3), {args.points} points, fp16, products {'f16' if args.m_f16 else 'f32'}: "
+          "stage entry points on the whole batch")
+    print("layer  C->K @ HxW        T      input us  TB/s | contract us  TB/s  MFMA TF | output us  TB/s")
+    for idx, (cin, cout) in enumerate(synth.VGG16_LAYERS, start=1):
+        x = torch.randn((N, cin, H, H), device=dev, generator=gen).abs().half()
+        w = (torch.randn((cout, cin, 3, 3), device=dev, generator=gen) * (2.0 / (9.0 * cin)) ** 0.5).half()
+        U = nova.nova_filter_transform(t, w)
+        V = nova.nova_input_transform(t, x)
+        M = nova.nova_contract(t, U, V, N, cin, H, H, cout, flags)
+        y = nova.nova_output_transform(t, M, N, cout, H, H, torch.float16, flags)
+        marks = []
+        for rep in range(args.reps + 3):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+            ev[0].record(); nova.nova_input_transform(t, x, V=V)
+            ev[1].record(); nova.nova_contract(t, U, V, N, cin, H, H, cout, flags, M=M)
+            ev[2].record(); nova.nova_output_transform(t, M, N, cout, H, H, torch.float16, flags, y=y)
+            ev[3].record()
+            if rep >= 3:
+                marks.append(ev)
+        torch.cuda.synchronize()
+        us = [sum(e[i].elapsed_time(e[i + 1]) for e in marks) / len(marks) * 1e3 for i in range(3)]
+        T = N * (-(-H // m)) ** 2
+        cp, kp = -(-cin // 32) * 32, -(-cout // 32) * 32
+        xb, yb = x.numel() * 2, y.numel() * 2
+        Vb, Ub, Mb = n * n * T * cp * 2, n * n * kp * cp * 2, n * n * T * kp * m_es
+        print(f"L{idx:<2d}   {cin:3d}->{cout:3d} @ {H:3d}x{H:<3d} {T:6d}   {us[0]:8.1f} {(xb + Vb) / us[0] / 1e6:5.2f} | "
+              f"{us[1]:9.1f} {(Ub + Vb + Mb) / us[1] / 1e6:5.2f} {2.0 * n * n * T * cin * cout / us[1] / 1e6:7.0f} | "
+              f"{us[2]:8.1f} {(Mb + yb) / us[2] / 1e6:5.2f}", flush=True)
+        del x, w, U, V, M, y
+        if idx in synth.VGG16_POOL_AFTER:
+            H //= 2
 
 
 def main():
@@ -23,7 +68,10 @@ def main():
     ap.add_argument("--separate-pool", action="store_true")
     ap.add_argument("--m-f16", action="store_true", help="keep the products M in binary16")
     ap.add_argument("--reps", type=int, default=10)
+    ap.add_argument("--stages", action="store_true", help="per-layer times of the three stage entry points")
     args = ap.parse_args()
+    if args.stages:
+        return stage_times(args)
 
     dev = "cuda:0"
     m, N = args.m, args.batch
