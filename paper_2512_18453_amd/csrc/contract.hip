@@ -187,10 +187,11 @@ contract_f16_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__
 __device__ __forceinline__ void stream_to_lds16(const void *uniform_base, unsigned byte_offset, unsigned lds_wave_base)
 {
     // lane i of the wave writes 16 bytes at LDS address lds_wave_base + 16*i (M0 = base).  M0 is a
-    // register the compiler reserves and sets itself right before each of its own uses (it has
-    // none in this kernel), so it is not listed as clobbered.
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 : : "s"(lds_wave_base), "v"(byte_offset), "s"(uniform_base) : "memory");
+    // register the compiler reserves for uses of its own and cannot be told about as clobbered, so
+    // the statement hands it back as it found it.
+    unsigned saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "s"(lds_wave_base), "v"(byte_offset), "s"(uniform_base) : "memory");
 }
 template <int IMM>
 __device__ __forceinline__ void stream_store(float *uniform_base, unsigned byte_offset, float a, float b, float c, float d)
@@ -302,7 +303,7 @@ contract_stream_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT 
                 const int r = (tid >> 2) + i * (THREADS / 4);    // row of the stage: [channel block][tile]
                 const int cb = r / SR, row = r % SR;             // SR is a power of two
                 int t = (tb0 + j) * SR + row; if (t > T - 1) t = T - 1;      // rows past the end: reread the last
-                const unsigned off = surplus ? 0u : (unsigned)(((cb * T + t) * kChanBlock + p_q * 8) * (int)sizeof(f16));
+                const unsigned off = surplus ? 0u : ((unsigned)(cb * T + t) * kChanBlock + (unsigned)p_q * 8u) * (unsigned)sizeof(f16);
                 stream_to_lds16(v_plane, off, ring_base + slot * STAGE_BYTES + (i * THREADS + wave * 64) * 16);
             }
         };
@@ -338,7 +339,7 @@ contract_stream_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT 
         MT *m_plane = uniform_pointer(Mo + ((size_t)xi * k_blocks + (size_t)(kg * WN + wn) * NB) * Tp * kChanBlock);
         // lane holds t = lane%32 and output channels 8*(e/4) + 4*(lane/32) + e%4 of each block:
         // four consecutive channels per store; rows up to Tp exist, so no store is conditional
-        unsigned m_off = (unsigned)(((tb0 * SR + wm * 32 + frag_row) * kChanBlock + (lane >> 5) * 4) * (int)sizeof(MT));
+        unsigned m_off = ((unsigned)(tb0 * SR + wm * 32 + frag_row) * kChanBlock + (unsigned)(lane >> 5) * 4u) * (unsigned)sizeof(MT);
         int slot = 0;
         for (int j = 0; j < count; ++j) {
             stream_wait_stage<0, S, NP, NS>(j);                // this wave's pieces of stage j have landed
@@ -378,7 +379,7 @@ contract_stream_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT 
                 stream_store<2 * 8 * (int)sizeof(MT)>(plane, m_off, acc[nb][8], acc[nb][9], acc[nb][10], acc[nb][11]);
                 stream_store<3 * 8 * (int)sizeof(MT)>(plane, m_off, acc[nb][12], acc[nb][13], acc[nb][14], acc[nb][15]);
             }
-            m_off += SR * kChanBlock * (int)sizeof(MT);
+            m_off += (unsigned)(SR * kChanBlock) * (unsigned)sizeof(MT);
             slot = slot == S - 1 ? 0 : slot + 1;
         }
         // the surplus prefetches of the tail must land before the ring is refilled or released,
