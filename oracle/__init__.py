@@ -23,8 +23,8 @@ conv        fp64 direct convolution (the definition, Sec. 2.1), fp64 Winograd
 Parity pins (see tests/test_oracle_*.py): every function here is pinned to
 something other than itself -- printed condition numbers, the textbook
 F(2,3)/F(4,3) algorithms, exact rational equality with direct convolution, a
-library fp64 convolution, and exact-rounding special cases of the emulation.
-The one exception: the general (inexact) case of the reduced-precision
-emulation has no printed value to compare with -- "parity unpinned" beyond
-those exact special cases and the error-ordering checks.
+library fp64 convolution, exact-rounding special cases of the emulation, and,
+for the emulation's general (inexact) case, a replay of its stated arithmetic
+contract in exact rational arithmetic with every rounding applied explicitly
+(tests/test_oracle_emulation_replay.py), which it must match bit for bit.
 """
