@@ -19,6 +19,7 @@ import pytest
 import torch
 
 from oracle import conv
+from oracle import cook_toom as ct
 from paper_2512_18453_amd import nova, synth
 
 pytestmark = pytest.mark.gpu
@@ -37,6 +38,63 @@ def pts(pairs):
 
 def rel_l2(a, b):
     return float(np.linalg.norm((a - b).ravel()) / max(np.linalg.norm(b.ravel()), 1e-300))
+
+
+def ulp16(v):
+    """Spacing of binary16 numbers at |v| (the sub-normal spacing 2^-24 below 2^-14)."""
+    a = np.maximum(np.abs(v), 2.0 ** -14)
+    return 2.0 ** (np.floor(np.log2(a)) - 10)
+
+
+def elementwise_fp16(got, emu, points, m, want_intermediates, C, what="y"):
+    """Element-by-element bars for a binary16 output against the emulation, beside the rel-L2 bar.
+
+    The two sides start from bit-identical U and V.  They differ in (i) the channel sum -- the matrix
+    unit adds C exact products in binary32 in an order of its own, the emulation in binary64: at most
+    C u |U||V| summed over c per entry of M in the standard model, u = 2^-24; (ii) one rounding of M
+    to binary32 on each side: 2 u |M|; (iii) the output transform, two nested sums of n terms in
+    binary32 against binary64: 2 n u |A|^T |M| |A|; (iv) the final rounding to binary16, which moves
+    two neighbouring values at most one binary16 spacing further apart.  With
+    P[xi] = sum_c |U[xi]| |V[xi]| >= |M[xi]| and w[xi] = |A[i][p]| |A[j][q]|:
+
+      worst case    |y_gpu - y_emu| <= ulp16(y) + 2 (C + 2 n + 2) u  sum_xi w P
+                    (every rounding error at its maximum and of the same sign; the factor 2 allows
+                    for intermediate sums of the matrix unit that are truncated, not rounded);
+      statistical   |y_gpu - y_emu| <= ulp16(y) + 8 sqrt(C + 2 n + 2) u  sqrt(sum_xi (w P)^2)
+                    (the C + 2 n + 2 rounding errors per position modelled as independent, zero
+                    mean, each below u times its position's term: the second summand is about
+                    8 sqrt(3) = 14 standard deviations of their sum, and 3 to 40 times narrower
+                    than the worst case, narrow enough that a single misplaced or stale output
+                    element -- wrong by about rms(y) -- fails it on every shape here).
+
+    Both must hold for every element, and non-finite values must sit at the same places.
+    Returns max |diff| / statistical bound and the median statistical bound relative to rms(y)."""
+    y_o, U_o, V_o, M_o = want_intermediates
+    n = int(round(np.sqrt(U_o.shape[0])))
+    r = n - m + 1
+    A = np.abs(ct.to_f32(ct.cook_toom(pts(points), m, r)[0]).astype(np.float64))      # n x m
+    N, K, H, W = emu.shape
+    th, tw = -(-H // m), -(-W // m)
+    P = np.matmul(np.abs(V_o), np.abs(U_o).transpose(0, 2, 1)).reshape(n, n, N * th * tw, K)
+
+    def to_image(per_tile):
+        return per_tile.reshape(N, th, tw, K, m, m).transpose(0, 3, 1, 4, 2, 5).reshape(N, K, th * m, tw * m)[:, :, :H, :W]
+
+    lin = to_image(np.einsum("ip,jq,ijtk->tkpq", A, A, P, optimize=True))
+    rss = to_image(np.sqrt(np.einsum("ip,jq,ijtk->tkpq", A * A, A * A, P * P, optimize=True)))
+    fin = np.isfinite(emu)
+    assert np.array_equal(np.isfinite(got), fin), f"{what}: non-finite values at different places"
+    spacing = ulp16(np.where(fin, np.maximum(np.abs(emu), np.abs(got)), 0.0))
+    terms = C + 2 * n + 2
+    worst = spacing + 2.0 * terms * 2.0 ** -24 * lin
+    stat = spacing + 8.0 * np.sqrt(terms) * 2.0 ** -24 * rss
+    diff = np.abs(np.where(fin, got - emu, 0.0))
+    for name, bound in (("worst-case", worst), ("statistical", stat)):
+        if (diff > bound).any():
+            idx = np.unravel_index(np.argmax(diff / bound), diff.shape)
+            raise AssertionError(f"{what}: element {idx} gpu {got[idx]!r} emulation {emu[idx]!r} "
+                                 f"{name} bound {bound[idx]:.3e}")
+    return float((diff / stat).max()), float(np.median(stat[fin]) / max(np.sqrt(np.mean(emu[fin] ** 2)), 1e-300))
 
 
 def same(got, want, what):
@@ -134,8 +192,8 @@ def test_fp16_stages_against_emulation(name, m, N, C, K, H, W):
     t = nova.nova_make_transforms(points, m, 3)
     got = run_stages(t, x, w)
     x64, w64 = x.astype(np.float64), w.astype(np.float64)
-    y_o, U_o, V_o, M_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=16,
-                                                      want_intermediates=True)
+    emu = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=16, want_intermediates=True)
+    y_o, U_o, V_o, M_o = emu
     same(got["U"], U_o, "U")
     same(got["V"], V_o, "V")
     assert rel_l2(got["M"], M_o) < 1e-5
@@ -143,6 +201,9 @@ def test_fp16_stages_against_emulation(name, m, N, C, K, H, W):
     err = rel_l2(got["y"], y_o)
     say(f"  rel-L2 vs emulation {err:.3e}; vs fp64 definition {rel_l2(got['y'], conv.direct_conv2d(x64, w64)):.3e}")
     assert err < 5e-3
+    ratio, width = elementwise_fp16(got["y"], y_o, points, m, emu, C)
+    ratio2, _ = elementwise_fp16(got["y_conv"], y_o, points, m, emu, C, "y (single call)")
+    say(f"  element-wise: max |diff| / bound {ratio:.3f} (single call {ratio2:.3f}); median bound / rms(y) {width:.2e}")
 
 
 def test_fp32_small_layer_against_definition():
@@ -209,11 +270,14 @@ def test_generic_point_order_uses_the_same_contract():
         assert not t.symmetric
         x, w = synth.make_layer(2, 20, 12, 11, 18, seed=3, dtype="f16")
         got = run_stages(t, x, w)
-        y_o, U_o, V_o, M_o = conv.winograd_conv2d_emulated(x.astype(np.float64), w.astype(np.float64), pts(points), 4,
-                                                          storage=16, want_intermediates=True)
+        emu = conv.winograd_conv2d_emulated(x.astype(np.float64), w.astype(np.float64), pts(points), 4,
+                                            storage=16, want_intermediates=True)
+        y_o, U_o, V_o, M_o = emu
         same(got["U"], U_o, "U")
         same(got["V"], V_o, "V")
         assert rel_l2(got["y"], y_o) < 5e-3
+        elementwise_fp16(got["y"], y_o, points, 4, emu, 20)
+        elementwise_fp16(got["y_conv"], y_o, points, 4, emu, 20, "y (single call)")
 
 
 def test_flags_relu_and_fp16_products():
@@ -223,8 +287,11 @@ def test_flags_relu_and_fp16_products():
     t = nova.nova_make_transforms(points, 6, 3)
     x64, w64 = x.astype(np.float64), w.astype(np.float64)
     got = run_stages(t, x, w, flags=nova.NOVA_FLAG_RELU)
-    y_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), 6, storage=16, relu=True)
+    emu = conv.winograd_conv2d_emulated(x64, w64, pts(points), 6, storage=16, relu=True, want_intermediates=True)
+    y_o = emu[0]
     assert (got["y"] >= 0).all() and rel_l2(got["y"], y_o) < 5e-3
+    elementwise_fp16(got["y"], y_o, points, 6, emu, 48)          # (ReLU does not widen a difference)
+    elementwise_fp16(got["y_conv"], y_o, points, 6, emu, 48, "y (single call)")
     assert ((got["y"] == 0) == (y_o == 0)).mean() > 0.999
     got = run_stages(t, x, w, flags=nova.NOVA_FLAG_M_F16)
     y_o, _, _, M_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), 6, storage=16, m_storage=16,
@@ -255,13 +322,17 @@ def test_few_input_channels_single_call(m, C, K, H, W):
             y = nova.nova_winograd_conv2d(t, xd, U, K, flags=flags)
             x64, w64 = x.astype(np.float64), w.astype(np.float64)
             relu = bool(flags & nova.NOVA_FLAG_RELU)
-            y_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=storage, relu=relu,
-                                                m_storage=16 if flags & nova.NOVA_FLAG_M_F16 else 32)
+            emu = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=storage, relu=relu,
+                                                m_storage=16 if flags & nova.NOVA_FLAG_M_F16 else 32,
+                                                want_intermediates=True)
+            y_o = emu[0]
             want = conv.direct_conv2d(x64, w64)
             own = rel_l2(y_o, np.maximum(want, 0.0) if relu else want)
             err = rel_l2(y.cpu().numpy().astype(np.float64), y_o)
             say(f"  rel-L2 vs emulation {err:.3e} (emulation vs definition {own:.3e})")
             assert err < (5e-3 if storage == 16 else max(1e-5, 8 * own))
+            if storage == 16 and not flags & nova.NOVA_FLAG_M_F16:
+                elementwise_fp16(y.cpu().numpy().astype(np.float64), y_o, points, m, emu, C)
             if H % 2 == 0 and W % 2 == 0:
                 pooled = nova.nova_winograd_conv2d(t, xd, U, K, flags=flags | nova.NOVA_FLAG_POOL2)
                 assert torch.equal(pooled.float(), torch.nn.functional.max_pool2d(y.float(), 2))
@@ -466,10 +537,13 @@ def test_mid_layer_full_size():
         t = nova.nova_make_transforms(points, 6, 3)
         U = nova.nova_filter_transform(t, wd)
         y = nova.nova_winograd_conv2d(t, xd, U, cfg["K"]).cpu().numpy().astype(np.float64)
-        y_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), 6, storage=16)
+        emu = conv.winograd_conv2d_emulated(x64, w64, pts(points), 6, storage=16, want_intermediates=True)
+        y_o = emu[0]
         e_emu, e_def = rel_l2(y, y_o), rel_l2(y, want)
         say(f"  rel-L2 vs emulation {e_emu:.3e}; vs fp64 definition {e_def:.3e}")
         assert e_emu < 5e-3
+        ratio, width = elementwise_fp16(y, y_o, points, 6, emu, cfg["C"])
+        say(f"  element-wise: max |diff| / bound {ratio:.3f}; median bound / rms(y) {width:.2e}")
 
 
 def test_vgg_conv3_full_size_sampled_images():
@@ -489,11 +563,14 @@ def test_vgg_conv3_full_size_sampled_images():
         y = nova.nova_winograd_conv2d(t, xd, U, cfg["K"])
         torch.cuda.synchronize()
         y = y[sample].cpu().numpy().astype(np.float64)
-        y_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), 8, storage=16)
+        emu = conv.winograd_conv2d_emulated(x64, w64, pts(points), 8, storage=16, want_intermediates=(name == "nova"))
+        y_o = emu[0] if name == "nova" else emu
         if name == "nova":
             e_emu, e_def = rel_l2(y, y_o), rel_l2(y, want)
             say(f"  rel-L2 vs emulation {e_emu:.3e}; vs fp64 definition {e_def:.3e}")
             assert np.isfinite(y).all() and e_emu < 5e-3
+            ratio, width = elementwise_fp16(y, y_o, points, 8, emu, cfg["C"])
+            say(f"  element-wise: max |diff| / bound {ratio:.3f}; median bound / rms(y) {width:.2e}")
         else:
             bad, bad_o = ~np.isfinite(y), ~np.isfinite(y_o)
             say(f"  non-finite outputs: gpu {bad.mean():.3f} oracle {bad_o.mean():.3f}")
@@ -511,10 +588,13 @@ def test_resnet_shapes_reduced_batch():
         xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
         U = nova.nova_filter_transform(t, wd)
         y = nova.nova_winograd_conv2d(t, xd, U, ch).cpu().numpy().astype(np.float64)
-        y_o = conv.winograd_conv2d_emulated(x.astype(np.float64), w.astype(np.float64), pts(points), 8, storage=16)
+        emu = conv.winograd_conv2d_emulated(x.astype(np.float64), w.astype(np.float64), pts(points), 8, storage=16,
+                                            want_intermediates=True)
+        y_o = emu[0]
         err = rel_l2(y, y_o)
         say(f"  rel-L2 vs emulation {err:.3e}")
         assert np.isfinite(y).all() and err < 5e-3
+        elementwise_fp16(y, y_o, points, 8, emu, ch)
 
 
 @pytest.mark.parametrize("m", [6, 8])
@@ -532,11 +612,14 @@ def test_vgg_stack_reduced_size(m):
         U = nova.nova_filter_transform(t, torch.from_numpy(w).to(DEV))
         y = nova.nova_winograd_conv2d(t, act, U, cout, flags=nova.NOVA_FLAG_RELU)
         x64 = act.cpu().numpy().astype(np.float64)
-        y_o = conv.winograd_conv2d_emulated(x64, w.astype(np.float64), pts(points), m, storage=16, relu=True)
+        emu = conv.winograd_conv2d_emulated(x64, w.astype(np.float64), pts(points), m, storage=16, relu=True,
+                                            want_intermediates=True)
+        y_o = emu[0]
         got = y.cpu().numpy().astype(np.float64)
         err = rel_l2(got, y_o)
         say(f"  rel-L2 vs emulation {err:.3e}")
         assert np.isfinite(got).all() and err < 5e-3
+        elementwise_fp16(got, y_o, points, m, emu, cin)
         if layer in synth.VGG16_POOL_AFTER:
             pooled = nova.nova_relu_maxpool2x2(y)
             assert np.array_equal(pooled.cpu().numpy().astype(np.float64), conv.relu_maxpool2x2(got))
@@ -558,11 +641,14 @@ def test_resnet_shapes_full_batch_sampled_images():
         y = nova.nova_winograd_conv2d(t, xd, U, ch)
         torch.cuda.synchronize()
         got = y[sample].cpu().numpy().astype(np.float64)
-        y_o = conv.winograd_conv2d_emulated(x[sample].astype(np.float64), w.astype(np.float64), pts(points), 8,
-                                            storage=16)
+        emu = conv.winograd_conv2d_emulated(x[sample].astype(np.float64), w.astype(np.float64), pts(points), 8,
+                                            storage=16, want_intermediates=True)
+        y_o = emu[0]
         err = rel_l2(got, y_o)
         say(f"  rel-L2 vs emulation {err:.3e}")
         assert np.isfinite(got).all() and err < 5e-3
+        ratio, width = elementwise_fp16(got, y_o, points, 8, emu, ch)
+        say(f"  element-wise: max |diff| / bound {ratio:.3f}; median bound / rms(y) {width:.2e}")
         del xd, y
 
 
@@ -582,11 +668,16 @@ def test_vgg_stack_full_size_sampled_images(m):
         y = nova.nova_winograd_conv2d(t, act, U, cout, flags=nova.NOVA_FLAG_RELU)
         torch.cuda.synchronize()
         x64 = act[sample].cpu().numpy().astype(np.float64)
-        y_o = conv.winograd_conv2d_emulated(x64, w.astype(np.float64), pts(points), m, storage=16, relu=True)
+        emu = conv.winograd_conv2d_emulated(x64, w.astype(np.float64), pts(points), m, storage=16, relu=True,
+                                            want_intermediates=True)
+        y_o = emu[0]
         got = y[sample].cpu().numpy().astype(np.float64)
         err = rel_l2(got, y_o)
         say(f"  rel-L2 vs emulation {err:.3e}")
         assert np.isfinite(got).all() and err < 5e-3
+        ratio, width = elementwise_fp16(got, y_o, points, m, emu, cin)
+        say(f"  element-wise: max |diff| / bound {ratio:.3f}; median bound / rms(y) {width:.2e}")
+        del emu
         if layer in synth.VGG16_POOL_AFTER:
             pooled = nova.nova_relu_maxpool2x2(y)
             assert np.array_equal(pooled[sample].cpu().numpy().astype(np.float64), conv.relu_maxpool2x2(got))
@@ -626,7 +717,8 @@ def test_r5_fp16_stages_against_emulation(m, pset, N, C, K, H, W):
     assert (t.n, t.r, t.symmetric) == (m + 4, 5, True)
     got = run_stages(t, x, w)
     x64, w64 = x.astype(np.float64), w.astype(np.float64)
-    y_o, U_o, V_o, M_o = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=16, want_intermediates=True)
+    emu = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=16, want_intermediates=True)
+    y_o, U_o, V_o, M_o = emu
     same(got["U"], U_o, "U")
     same(got["V"], V_o, "V")
     assert rel_l2(got["M"], M_o) < 1e-5
@@ -634,6 +726,8 @@ def test_r5_fp16_stages_against_emulation(m, pset, N, C, K, H, W):
     err = rel_l2(got["y"], y_o)
     say(f"  rel-L2 vs emulation {err:.3e}; vs fp64 definition {rel_l2(got['y'], conv.direct_conv2d(x64, w64)):.3e}")
     assert err < 5e-3
+    elementwise_fp16(got["y"], y_o, points, m, emu, C)
+    elementwise_fp16(got["y_conv"], y_o, points, m, emu, C, "y (single call)")
 
 
 @pytest.mark.parametrize("m,pset", [(2, ("standard", 4)), (4, ("nova", 6)), (6, ("nova", 8))])
@@ -654,6 +748,42 @@ def test_r5_fp32_against_definition(m, pset):
     assert err <= max(1e-5, 4 * own)
     if m == 2:
         assert rel_l2(got["y"], want) <= 1e-5 and np.abs(got["y"] - want).max() <= 1e-4
+
+
+POISON_CASES = [
+    # m, N, C, K, H, W, dtype: T not a multiple of 128, K not a multiple of 32, C <= 4 and C > 4
+    (8, 3, 40, 33, 17, 23, "f16"),
+    (8, 2, 3, 5, 30, 41, "f16"),
+    (6, 5, 64, 70, 27, 56, "f16"),
+    (4, 3, 4, 20, 13, 9, "f32"),
+    (4, 2, 33, 50, 19, 22, "f32"),
+    (8, 7, 128, 64, 28, 28, "f16"),          # streaming contraction with a ragged last stage
+]
+
+
+@pytest.mark.parametrize("m,N,C,K,H,W,dtype", POISON_CASES)
+def test_poisoned_workspace_and_output_do_not_leak(m, N, C, K, H, W, dtype):
+    # The workspace (V, M, their padding rows and channels) and y are filled with NaN bit patterns
+    # before the call: whatever the kernels read they must have written first, and cropped regions
+    # (tile padding, channel padding, rows of M beyond T) must not reach y.  Two slab sizes.
+    say(f"[case] poisoned workspace F({m},3) {dtype} N={N} C={C} K={K} H={H} W={W}")
+    points = synth.point_set("nova", m)
+    t = nova.nova_make_transforms(points, m, 3)
+    x, w = synth.make_layer(N, C, K, H, W, seed=600 + m + C, dtype=dtype, x_dist="normal")
+    xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+    U = nova.nova_filter_transform(t, wd)
+    dt = nova.NOVA_F16 if dtype == "f16" else nova.NOVA_F32
+    for flags in (0, nova.NOVA_FLAG_RELU | (nova.NOVA_FLAG_M_F16 if dtype == "f16" else 0)):
+        for per_slab in (N, 1):
+            nbytes = nova.nova_conv2d_workspace_bytes(N, C, H, W, K, m, dt, flags, per_slab)
+            clean = torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
+            want = nova.nova_winograd_conv2d(t, xd, U, K, flags=flags, workspace=clean)
+            dirty = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=DEV)     # 0xFFFF / 0xFFFFFFFF: NaN
+            got = torch.full_like(want, float("nan"))
+            nova.nova_winograd_conv2d(t, xd, U, K, y=got, flags=flags, workspace=dirty)
+            torch.cuda.synchronize()
+            assert torch.isfinite(got).all(), f"flags {flags}, {per_slab} images per slab"
+            assert torch.equal(got, want)
 
 
 def test_graph_capture_replays_match_eager():
