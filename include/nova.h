@@ -44,7 +44,8 @@ enum {
     NOVA_EOVERFLOW = -3,    /* an exact intermediate or matrix entry does not fit 64-bit num/den */
     NOVA_EVERIFY = -4,      /* the generated matrices fail the exact tensor identity (internal bug trap) */
     NOVA_ENOSPC = -5,       /* workspace too small */
-    NOVA_EUNSUPPORTED = -6, /* valid request the device path does not implement (m not in {2,4,6,8}, r != 3) */
+    NOVA_EUNSUPPORTED = -6, /* valid request the device path does not implement (tile sizes other than
+                               r = 3 with m in {2,4,6,8} and r = 5 with m in {2,4,6}) */
     NOVA_EHIP = -7,         /* a HIP call failed; see nova_last_hip_error() */
     NOVA_ENOMEM = -8        /* host allocation failed */
 };
@@ -218,6 +219,23 @@ size_t nova_conv2d_workspace_bytes(int N, int C, int H, int W, int K, int m, int
 int nova_winograd_conv2d(const nova_transforms *t, const void *x, const void *U, void *y,
                          int N, int C, int H, int W, int K, int dtype, int flags,
                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * nova_winograd_conv2d for callers that cannot allocate device memory or carry a workspace around:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, result and errors, but V and M of a slab live in a fixed array of
+ * nova_static_workspace_bytes() = 64 MiB inside the library's device image (one copy per GPU, held
+ * until the process ends) instead of a caller buffer; the batch is cut into as many slabs of whole
+ * images as that size requires.  NOVA_ENOSPC if V and M of a single image exceed it (the shape then
+ * needs nova_winograd_conv2d with a workspace of its own).  The call allocates and frees nothing;
+ * the array's device address is looked up once per device (NOVA_EHIP if that fails).
+ * All calls on one GPU share that GPU's array and nothing in it is expected to be zero or to
+ * survive between calls: calls that overlap in time on one GPU (different streams, or threads)
+ * race on it and must be serialised by the caller.
+ */
+size_t nova_static_workspace_bytes(void);
+int nova_winograd_conv2d_static(const nova_transforms *t, const void *x, const void *U, void *y,
+                                int N, int C, int H, int W, int K, int dtype, int flags, void *stream);
 
 /* The three stages on their own (same arguments; V, M: device buffers for the N images passed).
  * V_bytes / M_bytes give the size of the buffer the call writes; the call returns NOVA_ENOSPC

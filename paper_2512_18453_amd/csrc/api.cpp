@@ -151,9 +151,10 @@ extern "C" int nova_output_transform(const nova_transforms *t, const void *M, si
     return hip_result(launch_output_transform(t, M, y, g, dtype, flags, stream));
 }
 
-extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, const void *U, void *y, int N,
-                                    int C, int H, int W, int K, int dtype, int flags, void *workspace,
-                                    size_t workspace_bytes, void *stream)
+// The slab loop behind nova_winograd_conv2d and nova_winograd_conv2d_static.
+int nova::conv2d_with_workspace(const nova_transforms *t, const void *x, const void *U, void *y, int N,
+                                int C, int H, int W, int K, int dtype, int flags, void *workspace,
+                                size_t workspace_bytes, void *stream)
 {
     if (int rc = check_handle(t)) return rc;
     if (!x || !U || !y || !workspace || !dims_ok(N, C, H, W, K) || !dtype_ok(dtype)) return NOVA_EINVAL;
@@ -202,6 +203,13 @@ extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, con
         if (int err = launch_output_transform(t, Mbuf, ys, g, dtype, flags, stream)) return hip_result(err);
     }
     return NOVA_OK;
+}
+
+extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, const void *U, void *y, int N,
+                                    int C, int H, int W, int K, int dtype, int flags, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    return conv2d_with_workspace(t, x, U, y, N, C, H, W, K, dtype, flags, workspace, workspace_bytes, stream);
 }
 
 extern "C" int nova_relu_maxpool2x2(const void *in, void *out, int N, int C, int H, int W, int dtype,

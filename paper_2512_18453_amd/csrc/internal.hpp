@@ -96,6 +96,9 @@ void set_last_hip_error(int err);
 // sigma_max / sigma_min of a row-major matrix (one-sided Jacobi)
 double spectral_condition(const std::vector<double> &mat, int rows, int cols);
 int device_cu_count();          // compute units of the current device (256 if the query fails)
+// nova_winograd_conv2d's argument checks and slab loop; returns a NOVA_* code
+int conv2d_with_workspace(const nova_transforms *t, const void *x, const void *U, void *y, int N, int C, int H,
+                          int W, int K, int dtype, int flags, void *workspace, size_t workspace_bytes, void *stream);
 
 int launch_filter_transform(const nova_transforms *t, const void *w, int K, int C, int dtype,
                             void *U, void *stream);

@@ -24,6 +24,7 @@ EXPORTS = [
     "nova_make_transforms", "nova_make_transforms_ex", "nova_get_row_scaling", "nova_get_matrix_int8", "nova_free_transforms", "nova_symmetric_search", "nova_snap_to_rational", "nova_transforms_shape", "nova_get_matrix",
     "nova_get_matrix_f64", "nova_get_matrix_f32", "nova_kappa", "nova_filter_bytes", "nova_input_bytes",
     "nova_product_bytes", "nova_filter_transform", "nova_conv2d_workspace_bytes", "nova_winograd_conv2d",
+    "nova_winograd_conv2d_static", "nova_static_workspace_bytes",
     "nova_input_transform", "nova_contract", "nova_output_transform", "nova_relu_maxpool2x2",
     "nova_strerror", "nova_last_hip_error", "nova_version",
 ]
@@ -74,6 +75,9 @@ def lib():
         L.nova_conv2d_workspace_bytes.restype = sz
         L.nova_filter_transform.argtypes = [vp, vp, i, i, i, vp, vp]
         L.nova_winograd_conv2d.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, vp, sz, vp]
+        L.nova_winograd_conv2d_static.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        L.nova_static_workspace_bytes.argtypes = []
+        L.nova_static_workspace_bytes.restype = sz
         L.nova_input_transform.argtypes = [vp, vp, vp, sz, i, i, i, i, i, vp]
         L.nova_contract.argtypes = [vp, vp, vp, vp, sz, i, i, i, i, i, i, i, vp]
         L.nova_output_transform.argtypes = [vp, vp, sz, vp, i, i, i, i, i, i, vp]
@@ -263,6 +267,18 @@ def nova_winograd_conv2d(t, x, U, K, y=None, flags=0, workspace=None, images_per
                                 dtype=torch.uint8, device=x.device)
     _check(lib().nova_winograd_conv2d(t.handle, _dev(x), _dev(U), _dev(y), N, C, H, W, K, dt, flags,
                                       _dev(workspace), workspace.numel(), _stream()), "nova_winograd_conv2d")
+    return y
+
+
+def nova_static_workspace_bytes():
+    return int(lib().nova_static_workspace_bytes())
+
+
+def nova_winograd_conv2d_static(t, x, U, K, y, flags=0):
+    """The call that allocates nothing: y must be passed in."""
+    N, C, H, W = x.shape
+    _check(lib().nova_winograd_conv2d_static(t.handle, _dev(x), _dev(U), _dev(y), N, C, H, W, K, _dtype_code(x),
+                                             flags, _stream()), "nova_winograd_conv2d_static")
     return y
 
 
