@@ -1,9 +1,11 @@
 #!/usr/bin/env python3
-"""Benchmark of the Winograd F(8 x 8, 3 x 3) hot path on one MI355X.
+"""Benchmark of the Winograd F(m x m, 3 x 3) hot path on one MI355X.
 
-A step is one nova_winograd_conv2d call (input transform -> 100 channel contractions -> output
-transform) on the VGG-16 conv3 shape (N=32, C=K=256, 56x56, fp16 storage, fp32 accumulation,
-NOVA points), inputs resident in HBM; the filter transform is done once outside the timed region.
+A step is one nova_winograd_conv2d call (input transform -> n*n channel contractions -> output
+transform), inputs resident in HBM; the filter transform is done once outside the timed region.
+Default workload, the headline: the VGG-16 conv3 shape (N=32, C=K=256, 56x56, F(8,3), fp16 storage,
+fp32 accumulation, NOVA points); --workload selects the other single-layer configurations (the small
+fp32 F(4,3) layer, the F(6,3) layer, the ResNet-style shapes at batch 256).
 Prints ONE JSON line: effective TFLOP/s counted in direct-convolution FLOPs, the roofline figure
 of the dominant kernel, per-stage figures, the fp16 error against the fp64 definition, and the
 CPU oracle's direct convolution timed on the host cores on a bounded sample of the same tensors.
@@ -22,18 +24,24 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_F16_PEAK_TFLOPS = 2500.0  # dense fp16 MFMA
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the
-# same counters read for a plain 256 MiB copy (FETCH_SIZE x 1.9998, WRITE_SIZE x 1.0000); see
-# profiles/vgg_conv3_f83_fp16_hbm_traffic.txt.  Keyed by (workload, points, products dtype,
-# images per slab, stage); anything not measured reports null.
-MEASURED_TRAFFIC_BYTES = {
-    ("vgg_conv3_f83_fp16", "nova", "f32", 32, "input_transform"): 133487818,
-    ("vgg_conv3_f83_fp16", "nova", "f32", 32, "contract"): 256229368,
-    ("vgg_conv3_f83_fp16", "nova", "f32", 32, "output_transform"): 212141825,
-    ("vgg_conv3_f83_fp16", "nova", "f16", 32, "input_transform"): 132316851,
-    ("vgg_conv3_f83_fp16", "nova", "f16", 32, "contract"): 175330453,
-    ("vgg_conv3_f83_fp16", "nova", "f16", 32, "output_transform"): 132427318,
-}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_table.txt")
+
+
+def measured_traffic(version, workload, points, products, images_per_slab, stage):
+    """HBM bytes per launch of one stage kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (scaled by what the same counters read for a plain copy; the commands are in the table's header).
+    The table is keyed by the library version the counters were collected with: a figure taken with
+    other kernels than the ones loaded now is not reported (None)."""
+    try:
+        with open(TRAFFIC_TABLE) as fh:
+            for line in fh:
+                cells = [c.strip() for c in line.split("|")]
+                if len(cells) == 7 and not line.startswith("#") and \
+                        cells[:6] == [version, workload, points, products, str(images_per_slab), stage]:
+                    return int(cells[6])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -41,8 +49,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="vgg_conv3_f83_fp16")
-    ap.add_argument("--points", default="nova")
+    ap.add_argument("--workload", default="vgg_conv3_f83_fp16",
+                    help="one of paper_2512_18453_amd.synth.LAYER_CONFIGS; the default is the headline workload")
+    ap.add_argument("--points", default=None, help="standard | nova | classic_half (F(6,3)) | dyadic (F(4,3))")
     ap.add_argument("--images-per-slab", type=int, default=0, help="0 = library default")
     ap.add_argument("--m-f16", action="store_true", help="keep the products M in fp16 (NOVA_FLAG_M_F16)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg (profiling runs)")
@@ -61,6 +70,8 @@ def main():
     from paper_2512_18453_amd import nova, synth
 
     cfg = synth.LAYER_CONFIGS[args.workload]
+    if args.points is None:
+        args.points = synth.DEFAULT_POINTS.get(args.workload, "nova")
     N, C, K, H, W, m = cfg["N"], cfg["C"], cfg["K"], cfg["H"], cfg["W"], cfg["m"]
     n = m + 2
     tdtype = torch.float16 if cfg["dtype"] == "f16" else torch.float32
@@ -143,11 +154,18 @@ def main():
         st["hbm_frac"] = st["gbs"] / HBM_PEAK_GBS
     dominant = max(stages, key=lambda k: stages[k]["us"])
     dom = stages[dominant]
-    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, args.points, "f16" if m_es == 2 else "f32",
-                                          int(slab_imgs), dominant))
+    traffic = measured_traffic(nova.nova_version(), args.workload, args.points, "f16" if m_es == 2 else "f32",
+                               int(slab_imgs), dominant)
     roofline = dict(kernel=dominant, bound="hbm", achieved=round(dom["gbs"], 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(dom["gbs"] / HBM_PEAK_GBS, 4), traffic=traffic,
                     launch_us=round(dom["us"], 2), algorithmic_bytes=dom["bytes"])
+    # the contraction against both of its bounds: the matrix cores' peak, and what its operand and
+    # result bytes allow at the HBM peak (the binding one at these shapes)
+    c_st = stages["contract"]
+    c_floor_us = max(gemm_flop / (MFMA_F16_PEAK_TFLOPS * 1e12), c_st["bytes"] / (HBM_PEAK_GBS * 1e9)) * 1e6
+    c_st["attainable_us"] = c_floor_us
+    c_st["frac_of_attainable"] = c_floor_us / c_st["us"]
+    c_st["binding"] = "hbm" if c_st["bytes"] / (HBM_PEAK_GBS * 1e9) > gemm_flop / (MFMA_F16_PEAK_TFLOPS * 1e12) else "mfma"
 
     # ---- the same K steps replayed from a HIP graph (10 steps per graph): what the step costs once the
     # host-side launch work is taken out; reported beside the headline, never as `value`
@@ -225,6 +243,22 @@ def main():
         cpu_baseline = dict(value=round(cpu_flop / cpu_s / 1e12, 6), unit="TFLOP/s", cores=oracle_conv.threads(),
                             kind="oracle", sample=f"fp64 direct conv of images 0..{n_cpu - 1} of {N} "
                             f"({cpu_flop / 1e9:.1f} GFLOP in {cpu_s:.2f} s, OpenMP)")
+        # the oracle's fp64 Winograd beside it, on as many images as take a few seconds (same FLOP count:
+        # the direct convolution's, so the two figures compare as times)
+        n_w = max(1, min(n_cpu, 2))
+        tic = time.perf_counter()
+        wino = oracle_conv.winograd_conv2d_f64(x[:n_w].astype(np.float64), w64, [Fraction(a, b) for a, b in points], m)
+        w_s = time.perf_counter() - tic
+        if w_s < 2.0 and n_w < n_cpu:
+            n_w = int(min(n_cpu, max(n_w, round(n_w * 4.0 / max(w_s, 1e-3)))))
+            tic = time.perf_counter()
+            wino = oracle_conv.winograd_conv2d_f64(x[:n_w].astype(np.float64), w64, [Fraction(a, b) for a, b in points], m)
+            w_s = time.perf_counter() - tic
+        cpu_baseline["winograd_f64"] = dict(
+            value=round(2.0 * n_w * K * C * H * W * 9 / w_s / 1e12, 6), unit="TFLOP/s (direct-conv FLOPs)",
+            sample=f"fp64 Winograd F({m},3) of images 0..{n_w - 1} in {w_s:.2f} s",
+            rel_l2_vs_direct=float(np.linalg.norm(wino - ref[:n_w]) / np.linalg.norm(ref[:n_w])))
+        del wino
         got = y[:n_cpu].cpu().numpy().astype(np.float64)
         fin = np.isfinite(got)
         result_extra["nonfinite_frac"] = float(1.0 - fin.mean())
@@ -242,7 +276,8 @@ def main():
         del ref1
 
     out = {
-        "metric": "effective TFLOP/s (direct-conv FLOPs), F(8,3) VGG-16 3x3 layer",
+        "metric": "effective TFLOP/s (direct-conv FLOPs), F(8,3) VGG-16 3x3 layer" if args.workload == "vgg_conv3_f83_fp16"
+                  else f"effective TFLOP/s (direct-conv FLOPs), {args.workload}",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16" if dt == nova.NOVA_F16 else "f32", "data": "synthetic",

@@ -186,12 +186,7 @@ contract_f16_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, MT *__
 // per access instead of two, which this kernel's register budget needs.
 __device__ __forceinline__ void stream_to_lds16(const void *uniform_base, unsigned byte_offset, unsigned lds_wave_base)
 {
-    // lane i of the wave writes 16 bytes at LDS address lds_wave_base + 16*i (M0 = base).  M0 is a
-    // register the compiler reserves for uses of its own and cannot be told about as clobbered, so
-    // the statement hands it back as it found it.
-    unsigned saved_m0;
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
-                 : "=&s"(saved_m0) : "s"(lds_wave_base), "v"(byte_offset), "s"(uniform_base) : "memory");
+    global_to_lds16<false>(uniform_base, byte_offset, lds_wave_base);
 }
 template <int IMM>
 __device__ __forceinline__ void stream_store(float *uniform_base, unsigned byte_offset, float a, float b, float c, float d)

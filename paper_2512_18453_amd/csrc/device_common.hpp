@@ -77,6 +77,39 @@ __device__ __forceinline__ P *uniform_pointer(P *p)
     return reinterpret_cast<P *>(((unsigned long long)hi << 32) | lo);
 }
 
+// One 16-byte piece per lane from global memory straight into LDS (no destination registers):
+// lane i of the wave reads uniform_base + byte_offset (its own) and writes LDS address
+// lds_wave_base + 16 * i; lanes switched off by the execution mask do neither.  The hardware takes
+// the LDS base from M0, a register the compiler reserves for uses of its own and cannot be told
+// about as clobbered, so the statement hands it back as it found it.  The load counts in vmcnt like
+// any vector-memory load; the compiler does not know that it writes LDS, so whoever reads that
+// memory waits (s_waitcnt vmcnt) and synchronises explicitly.  NT: streaming cache hint.
+template <bool NT>
+__device__ __forceinline__ void global_to_lds16(const void *uniform_base, unsigned byte_offset, unsigned lds_wave_base)
+{
+    unsigned saved_m0;
+    if constexpr (NT)
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3 nt\n\ts_mov_b32 m0, %0"
+                     : "=&s"(saved_m0) : "s"(lds_wave_base), "v"(byte_offset), "s"(uniform_base) : "memory");
+    else
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+                     : "=&s"(saved_m0) : "s"(lds_wave_base), "v"(byte_offset), "s"(uniform_base) : "memory");
+}
+
+// s_waitcnt vmcnt(n) for a wave-uniform run-time n: waits until at most min(n, 31) of the wave's
+// vector-memory operations are outstanding (the count is an immediate of the instruction, hence the
+// ladder; waiting for fewer than n is always safe).
+template <int LIMIT = 31>
+__device__ __forceinline__ void wait_vmcnt_at_most(int n)
+{
+    if constexpr (LIMIT == 0) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else {
+        if (n >= LIMIT) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(LIMIT) : "memory");
+        else wait_vmcnt_at_most<LIMIT - 1>(n);
+    }
+}
+
 // blockIdx.x -> logical block id such that consecutive logical ids run on the same XCD
 // (hardware deals consecutive workgroup ids round-robin over the 8 XCDs, each with its own L2).
 __device__ __forceinline__ unsigned xcd_local_block_id(unsigned id, unsigned total)

@@ -74,6 +74,11 @@ LAYER_CONFIGS = {
 
 # ResNet-50-style stride-1 3x3 bottleneck shapes at batch 256, F(8,3).
 RESNET_SHAPES = [(64, 56), (128, 28), (256, 14), (512, 7)]
+for _idx, (_ch, _hw) in enumerate(RESNET_SHAPES):
+    LAYER_CONFIGS[f"resnet_c{_ch}_{_hw}_f83_fp16"] = dict(N=256, C=_ch, K=_ch, H=_hw, W=_hw, m=8, dtype="f16",
+                                                         x_dist="half_normal", seed=5100 + _idx)
+# the point set each single-layer workload is quoted on (others can be asked for)
+DEFAULT_POINTS = {"small_f43_fp32": "standard", "mid_f63_fp16": "nova"}
 
 # VGG-16 conv stack: (C_in, C_out) per layer, 2x2 max-pool after layers 2, 4, 7, 10, 13.
 VGG16_LAYERS = [(3, 64), (64, 64), (64, 128), (128, 128), (128, 256), (256, 256), (256, 256),

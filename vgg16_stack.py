@@ -4,7 +4,7 @@ N(0,1) input, ReLU fused into every layer, 2x2 max-pool after layers 2, 4, 7, 10
 output transform, or as the separate kernel with --separate-pool).  Prints one JSON line with the
 time of a forward pass and the per-layer times.
 
-    python -m paper_2512_18453_amd.vgg16_stack [--m 8] [--batch 32] [--points nova] [--separate-pool] [--m-f16]
+    python vgg16_stack.py [--m 8] [--batch 32] [--points nova] [--separate-pool] [--m-f16]
 
 With --stages it times, layer by layer, the three stage entry points on the whole batch (no slabs, the
 products in binary32 or binary16 as chosen) and prints one line per layer: time and algorithmic
@@ -15,7 +15,14 @@ import json
 
 import torch
 
-from . import nova, synth
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2512_18453_amd import nova, synth  # noqa: E402
 
 
 def stage_times(args):
