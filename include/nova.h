@@ -248,6 +248,53 @@ int nova_contract(const nova_transforms *t, const void *U, const void *V, void *
 int nova_output_transform(const nova_transforms *t, const void *M, size_t M_bytes, void *y,
                           int N, int K, int H, int W, int dtype, int flags, void *stream); /* step 4 */
 
+/*
+ * INT8 operands in the Winograd domain (Sec. 4.1 "INT8 Setup"; paragraph "CNN Quantization Setup":
+ * the transform matrices stay in floating point, what is quantised are the weights and the
+ * Winograd-domain tensors).  Symmetric quantisation without zero point: scale s = max|.| / 127,
+ * code = value / s rounded to nearest (ties to even) and saturated to [-128, 127]; every
+ * floating-point step that decides a code is binary32 and correctly rounded; a tensor (or channel)
+ * that is all zero gets s = 1.  mode:
+ *   NOVA_INT8_PER_TENSOR   one scale for U, one for V
+ *   NOVA_INT8_PER_CHANNEL  one scale of U per output channel k (over all positions and input
+ *                          channels), one for V (a scale that varied with the input channel could
+ *                          not be pulled out of the channel sum)
+ *   NOVA_INT8_PER_POSITION one scale per Winograd-domain position xi, for U and for V (n*n scales
+ *                          each): the tap-wise scaling of the paper's related-work discussion
+ * The channel contraction then runs on the codes, exactly, on the integer matrix cores:
+ *   Mi[xi][t][k] = sum_c Vq[xi][t][c] Uq[xi][k][c]  (32-bit),  M = fl(fl(Mi) * fl(s_U[k] * s_V)).
+ * Layouts as for U, V, M above with one byte per element (Uq, Vq) and 4 bytes per element (Mi, M).
+ *
+ * nova_quantize_filter_int8: U from nova_filter_transform (dtype) -> Uq (nova_filter_int8_bytes) and
+ *   u_scales (device: 1 float, K floats, or n*n floats, by mode).  Once per weight set.
+ * nova_quantize_input_int8: V from nova_input_transform (dtype, the N images passed) -> Vq
+ *   (nova_input_int8_bytes) and v_scale (device: 1 float, or n*n floats per position; taken over
+ *   these N images).
+ * nova_contract_int8: M (device, nova_product_bytes(.., NOVA_F32, 0) bytes) receives the exact 32-bit
+ *   sums (dequantise = 0; the scale pointers may then be NULL) or the de-quantised binary32 products
+ *   (dequantise = 1), which nova_output_transform takes as they are.
+ * nova_winograd_conv2d_int8: input transform, quantisation of V (one scale for the whole batch of
+ *   the call), integer contraction, output transform, in one call; x, y of dtype as in
+ *   nova_winograd_conv2d; workspace at least nova_conv2d_int8_workspace_bytes, 256-byte aligned; the
+ *   batch is not cut into slabs (the scale of V belongs to the whole call).  NOVA_FLAG_M_F16 is
+ *   refused (NOVA_EINVAL).
+ * All are asynchronous on `stream` and allocate nothing.  Errors as for the calls above.
+ */
+enum { NOVA_INT8_PER_TENSOR = 0, NOVA_INT8_PER_CHANNEL = 1, NOVA_INT8_PER_POSITION = 2 };
+size_t nova_filter_int8_bytes(int K, int C, int m, int r);
+size_t nova_input_int8_bytes(int N, int C, int H, int W, int m, int r);
+int nova_quantize_filter_int8(const nova_transforms *t, const void *U, int K, int C, int dtype, int mode,
+                              void *Uq, float *u_scales, void *stream);
+int nova_quantize_input_int8(const nova_transforms *t, const void *V, int N, int C, int H, int W, int dtype,
+                             int mode, void *Vq, float *v_scale, void *stream);
+int nova_contract_int8(const nova_transforms *t, const void *Uq, const void *Vq, const float *u_scales,
+                       const float *v_scale, int mode, void *M, size_t M_bytes, int N, int C, int H, int W, int K,
+                       int dequantise, void *stream);
+size_t nova_conv2d_int8_workspace_bytes(int N, int C, int H, int W, int K, int m, int r, int dtype);
+int nova_winograd_conv2d_int8(const nova_transforms *t, const void *x, const void *Uq, const float *u_scales,
+                              int mode, void *y, int N, int C, int H, int W, int K, int dtype, int flags,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
 /* out = maxpool2x2(max(in, 0)), stride 2, floor; in [N][C][H][W] -> out [N][C][H/2][W/2] (device).
  * The step between the blocks of a VGG-style stack. */
 int nova_relu_maxpool2x2(const void *in, void *out, int N, int C, int H, int W, int dtype, void *stream);

@@ -212,6 +212,104 @@ extern "C" int nova_winograd_conv2d(const nova_transforms *t, const void *x, con
     return conv2d_with_workspace(t, x, U, y, N, C, H, W, K, dtype, flags, workspace, workspace_bytes, stream);
 }
 
+// ---- INT8 operands in the Winograd domain
+
+static bool int8_mode_ok(int mode)
+{
+    return mode == NOVA_INT8_PER_TENSOR || mode == NOVA_INT8_PER_CHANNEL || mode == NOVA_INT8_PER_POSITION;
+}
+
+extern "C" size_t nova_filter_int8_bytes(int K, int C, int m, int r)
+{
+    return nova_filter_bytes(K, C, m, r, NOVA_F16) / 2;
+}
+
+extern "C" size_t nova_input_int8_bytes(int N, int C, int H, int W, int m, int r)
+{
+    return nova_input_bytes(N, C, H, W, m, r, NOVA_F16) / 2;
+}
+
+extern "C" int nova_quantize_filter_int8(const nova_transforms *t, const void *U, int K, int C, int dtype, int mode,
+                                         void *Uq, float *u_scales, void *stream)
+{
+    if (int rc = check_handle(t)) return rc;
+    if (!U || !Uq || !u_scales || K < 1 || C < 1 || !dtype_ok(dtype) || !int8_mode_ok(mode)) return NOVA_EINVAL;
+    const Geometry g = make_geometry(1, C, 1, 1, K, t->m, t->r);
+    const long long elements = (long long)g.n * g.n * g.c_blocks * g.Kp * kChanBlock;
+    const int count = mode == NOVA_INT8_PER_CHANNEL ? K : mode == NOVA_INT8_PER_POSITION ? g.n * g.n : 1;
+    return hip_result(launch_quantize_int8(U, Uq, u_scales, elements, g.n * g.n, g.Kp, count, mode, dtype, stream));
+}
+
+extern "C" int nova_quantize_input_int8(const nova_transforms *t, const void *V, int N, int C, int H, int W, int dtype,
+                                        int mode, void *Vq, float *v_scale, void *stream)
+{
+    if (int rc = check_handle(t)) return rc;
+    if (!V || !Vq || !v_scale || !dims_ok(N, C, H, W, 1) || !dtype_ok(dtype) || !int8_mode_ok(mode)) return NOVA_EINVAL;
+    const Geometry g = make_geometry(N, C, H, W, 1, t->m, t->r);
+    if (g.T > 0x7fffffffLL) return NOVA_EINVAL;
+    const long long elements = (long long)g.n * g.n * g.c_blocks * g.T * kChanBlock;
+    const bool pos = mode == NOVA_INT8_PER_POSITION;
+    return hip_result(launch_quantize_int8(V, Vq, v_scale, elements, g.n * g.n, (int)g.T, pos ? g.n * g.n : 1, pos ? 2 : 0,
+                                           dtype, stream));
+}
+
+extern "C" int nova_contract_int8(const nova_transforms *t, const void *Uq, const void *Vq, const float *u_scales,
+                                  const float *v_scale, int mode, void *M, size_t M_bytes, int N, int C, int H, int W,
+                                  int K, int dequantise, void *stream)
+{
+    if (int rc = check_handle(t)) return rc;
+    if (!Uq || !Vq || !M || !dims_ok(N, C, H, W, K) || !int8_mode_ok(mode)) return NOVA_EINVAL;
+    if (dequantise && (!u_scales || !v_scale)) return NOVA_EINVAL;
+    const Geometry g = make_geometry(N, C, H, W, K, t->m, t->r);
+    if (M_bytes < m_bytes(g, NOVA_F32, 0)) return NOVA_ENOSPC;
+    return hip_result(launch_contract_int8(Uq, Vq, M, u_scales, v_scale, mode, dequantise ? 1 : 0, g, stream));
+}
+
+// workspace of nova_winograd_conv2d_int8: V (storage format) | Vq | its scale | M (binary32), each 256-byte aligned
+static size_t int8_parts(const Geometry &g, int dtype, size_t off[4])
+{
+    off[0] = 0;
+    off[1] = off[0] + align256(v_bytes(g, dtype));
+    off[2] = off[1] + align256(v_bytes(g, NOVA_F16) / 2);
+    off[3] = off[2] + align256((size_t)g.n * g.n * sizeof(float));
+    return off[3] + align256(m_bytes(g, NOVA_F32, 0));
+}
+
+extern "C" size_t nova_conv2d_int8_workspace_bytes(int N, int C, int H, int W, int K, int m, int r, int dtype)
+{
+    if (!dims_ok(N, C, H, W, K) || !device_tile_ok(m, r) || !dtype_ok(dtype)) return 0;
+    size_t off[4];
+    return int8_parts(make_geometry(N, C, H, W, K, m, r), dtype, off);
+}
+
+extern "C" int nova_winograd_conv2d_int8(const nova_transforms *t, const void *x, const void *Uq, const float *u_scales,
+                                         int mode, void *y, int N, int C, int H, int W, int K, int dtype, int flags,
+                                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (int rc = check_handle(t)) return rc;
+    if (!x || !Uq || !u_scales || !y || !workspace || !dims_ok(N, C, H, W, K) || !dtype_ok(dtype) || !int8_mode_ok(mode))
+        return NOVA_EINVAL;
+    if (((uintptr_t)workspace & 255) != 0 || (flags & NOVA_FLAG_M_F16)) return NOVA_EINVAL;
+    if ((flags & NOVA_FLAG_POOL2) && (H % 2 != 0 || W % 2 != 0)) return NOVA_EINVAL;
+    const Geometry g = make_geometry(N, C, H, W, K, t->m, t->r);
+    if (g.T > 0x7fffffffLL) return NOVA_EINVAL;
+    size_t off[4];
+    if (int8_parts(g, dtype, off) > workspace_bytes) return NOVA_ENOSPC;
+    char *ws = (char *)workspace;
+    void *V = ws + off[0], *Vq = ws + off[1], *Mf = ws + off[3];
+    float *v_scale = (float *)(ws + off[2]);
+    if (int err = launch_input_transform(t, x, V, g, dtype, stream)) return hip_result(err);
+    const long long elements = (long long)g.n * g.n * g.c_blocks * g.T * kChanBlock;
+    const bool pos = mode == NOVA_INT8_PER_POSITION;
+    if (int err = launch_quantize_int8(V, Vq, v_scale, elements, g.n * g.n, (int)g.T, pos ? g.n * g.n : 1, pos ? 2 : 0, dtype,
+                                       stream))
+        return hip_result(err);
+    if (int err = launch_contract_int8(Uq, Vq, Mf, u_scales, v_scale, mode, 1, g, stream)) return hip_result(err);
+    // the de-quantised products are binary32 whatever the storage format: the output transform's binary32-M path
+    if (int err = launch_output_transform(t, Mf, y, g, dtype, flags, stream)) return hip_result(err);
+    return NOVA_OK;
+}
+
 extern "C" int nova_relu_maxpool2x2(const void *in, void *out, int N, int C, int H, int W, int dtype,
                                     void *stream)
 {

@@ -120,6 +120,13 @@ int launch_input_transform_few(const nova_transforms *t, const void *x, void *Vc
 int launch_pack_few_channels(const void *U, void *Uc, const Geometry &g, int dtype, void *stream);
 int launch_output_transform_few(const nova_transforms *t, const void *V, const void *Uc, void *y,
                                 const Geometry &g, int dtype, int flags, void *stream);
+// INT8 operands in the Winograd domain: symmetric quantisation of a blocked tensor [positions][channel
+// blocks][rows][32] with one scale (kind 0), one per row index (1) or one per position (2); integer
+// contraction, raw (int32) or de-quantised (binary32) with the scales of the same kind
+int launch_quantize_int8(const void *src, void *dst, void *scales, long long elements, int positions, int rows,
+                         int n_scales, int kind, int dtype, void *stream);
+int launch_contract_int8(const void *Uq, const void *Vq, void *Mo, const void *u_scales, const void *v_scale,
+                         int scale_kind, int dequantise, const Geometry &g, void *stream);
 int launch_relu_maxpool2x2(const void *in, void *out, int N, int C, int H, int W, int dtype,
                            void *stream);
 }  // namespace nova

@@ -16,6 +16,7 @@ NOVA_MATRIX_A, NOVA_MATRIX_BT, NOVA_MATRIX_G = 0, 1, 2
 NOVA_ROWS_PLAIN, NOVA_ROWS_BALANCED, NOVA_ROWS_GIVEN = 0, 1, 2
 NOVA_MATRIX_F32, NOVA_MATRIX_F16, NOVA_MATRIX_INT8 = 0, 1, 2
 NOVA_FLAG_RELU, NOVA_FLAG_M_F16, NOVA_FLAG_POOL2 = 1, 2, 4
+NOVA_INT8_PER_TENSOR, NOVA_INT8_PER_CHANNEL, NOVA_INT8_PER_POSITION = 0, 1, 2
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnova.so")
 _lib = None
@@ -25,6 +26,8 @@ EXPORTS = [
     "nova_get_matrix_f64", "nova_get_matrix_f32", "nova_kappa", "nova_filter_bytes", "nova_input_bytes",
     "nova_product_bytes", "nova_filter_transform", "nova_conv2d_workspace_bytes", "nova_winograd_conv2d",
     "nova_winograd_conv2d_static", "nova_static_workspace_bytes",
+    "nova_filter_int8_bytes", "nova_input_int8_bytes", "nova_quantize_filter_int8", "nova_quantize_input_int8",
+    "nova_contract_int8", "nova_conv2d_int8_workspace_bytes", "nova_winograd_conv2d_int8",
     "nova_input_transform", "nova_contract", "nova_output_transform", "nova_relu_maxpool2x2",
     "nova_strerror", "nova_last_hip_error", "nova_version",
 ]
@@ -78,6 +81,16 @@ def lib():
         L.nova_winograd_conv2d_static.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         L.nova_static_workspace_bytes.argtypes = []
         L.nova_static_workspace_bytes.restype = sz
+        L.nova_filter_int8_bytes.argtypes = [i] * 4
+        L.nova_filter_int8_bytes.restype = sz
+        L.nova_input_int8_bytes.argtypes = [i] * 6
+        L.nova_input_int8_bytes.restype = sz
+        L.nova_quantize_filter_int8.argtypes = [vp, vp, i, i, i, i, vp, vp, vp]
+        L.nova_quantize_input_int8.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp, vp]
+        L.nova_contract_int8.argtypes = [vp, vp, vp, vp, vp, i, vp, sz, i, i, i, i, i, i, vp]
+        L.nova_conv2d_int8_workspace_bytes.argtypes = [i] * 8
+        L.nova_conv2d_int8_workspace_bytes.restype = sz
+        L.nova_winograd_conv2d_int8.argtypes = [vp, vp, vp, vp, i, vp, i, i, i, i, i, i, i, vp, sz, vp]
         L.nova_input_transform.argtypes = [vp, vp, vp, sz, i, i, i, i, i, vp]
         L.nova_contract.argtypes = [vp, vp, vp, vp, sz, i, i, i, i, i, i, i, vp]
         L.nova_output_transform.argtypes = [vp, vp, sz, vp, i, i, i, i, i, i, vp]
@@ -311,6 +324,54 @@ def nova_output_transform(t, M, N, K, H, W, dtype, flags=0, y=None):
         y = torch.empty((N, K) + out_hw, dtype=dtype, device=M.device)
     _check(lib().nova_output_transform(t.handle, _dev(M), M.numel() * M.element_size(), _dev(y), N, K, H, W, dt,
                                        flags, _stream()), "nova_output_transform")
+    return y
+
+
+def nova_quantize_filter_int8(t, U, K, C, mode=NOVA_INT8_PER_TENSOR):
+    """U (flat, from nova_filter_transform) -> (Uq int8 flat, u_scales float32 [1] or [K])."""
+    Uq = torch.empty(lib().nova_filter_int8_bytes(K, C, t.m, t.r), dtype=torch.int8, device=U.device)
+    count = K if mode == NOVA_INT8_PER_CHANNEL else t.n * t.n if mode == NOVA_INT8_PER_POSITION else 1
+    scales = torch.empty(count, dtype=torch.float32, device=U.device)
+    _check(lib().nova_quantize_filter_int8(t.handle, _dev(U), K, C, _dtype_code(U), mode, _dev(Uq), _dev(scales), _stream()),
+           "nova_quantize_filter_int8")
+    return Uq, scales
+
+
+def nova_quantize_input_int8(t, V, N, C, H, W, mode=NOVA_INT8_PER_TENSOR):
+    Vq = torch.empty(lib().nova_input_int8_bytes(N, C, H, W, t.m, t.r), dtype=torch.int8, device=V.device)
+    scale = torch.empty(t.n * t.n if mode == NOVA_INT8_PER_POSITION else 1, dtype=torch.float32, device=V.device)
+    _check(lib().nova_quantize_input_int8(t.handle, _dev(V), N, C, H, W, _dtype_code(V), mode, _dev(Vq), _dev(scale),
+                                          _stream()), "nova_quantize_input_int8")
+    return Vq, scale
+
+
+def nova_contract_int8(t, Uq, Vq, u_scales, v_scale, mode, N, C, H, W, K, dequantise, M=None):
+    if M is None:
+        nbytes = nova_product_bytes(N, K, H, W, t.m, NOVA_F32, 0, t.r)
+        M = torch.empty(nbytes // 4, dtype=torch.float32 if dequantise else torch.int32, device=Vq.device)
+    us = _dev(u_scales) if u_scales is not None else None
+    vs = _dev(v_scale) if v_scale is not None else None
+    _check(lib().nova_contract_int8(t.handle, _dev(Uq), _dev(Vq), us, vs, mode, _dev(M), M.numel() * 4, N, C, H, W, K,
+                                    1 if dequantise else 0, _stream()), "nova_contract_int8")
+    return M
+
+
+def nova_conv2d_int8_workspace_bytes(N, C, H, W, K, m, dtype, r=3):
+    return lib().nova_conv2d_int8_workspace_bytes(N, C, H, W, K, m, r, dtype)
+
+
+def nova_winograd_conv2d_int8(t, x, Uq, u_scales, mode, K, y=None, flags=0, workspace=None):
+    N, C, H, W = x.shape
+    dt = _dtype_code(x)
+    if y is None:
+        out_hw = (H // 2, W // 2) if flags & NOVA_FLAG_POOL2 else (H, W)
+        y = torch.empty((N, K) + out_hw, dtype=x.dtype, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(nova_conv2d_int8_workspace_bytes(N, C, H, W, K, t.m, dt, t.r), dtype=torch.uint8,
+                                device=x.device)
+    _check(lib().nova_winograd_conv2d_int8(t.handle, _dev(x), _dev(Uq), _dev(u_scales), mode, _dev(y), N, C, H, W, K, dt,
+                                           flags, _dev(workspace), workspace.numel(), _stream()),
+           "nova_winograd_conv2d_int8")
     return y
 
 

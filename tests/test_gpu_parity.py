@@ -18,7 +18,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import conv
+from oracle import conv, int8
 from oracle import cook_toom as ct
 from paper_2512_18453_amd import nova, synth
 
@@ -748,6 +748,96 @@ def test_r5_fp32_against_definition(m, pset):
     assert err <= max(1e-5, 4 * own)
     if m == 2:
         assert rel_l2(got["y"], want) <= 1e-5 and np.abs(got["y"] - want).max() <= 1e-4
+
+
+INT8_CASES = [
+    # name, m, N, C, K, H, W, dtype
+    ("standard", 2, 2, 8, 8, 7, 9, "f16"),
+    ("nova", 4, 3, 33, 70, 30, 41, "f16"),
+    ("nova", 4, 2, 64, 64, 20, 20, "f32"),
+    ("nova", 6, 2, 40, 130, 24, 56, "f16"),
+    ("nova", 8, 2, 72, 96, 33, 40, "f16"),
+    ("nova", 8, 1, 256, 256, 28, 28, "f16"),
+    ("standard", 4, 1, 3, 5, 17, 22, "f32"),
+]
+
+
+@pytest.mark.parametrize("name,m,N,C,K,H,W,dtype", INT8_CASES)
+def test_int8_winograd_domain_against_the_oracle(name, m, N, C, K, H, W, dtype):
+    # Codes, scales and the 32-bit channel sums are integers (or binary32 numbers decided by the same
+    # correctly rounded binary32 steps on both sides): bit-exact.  The output goes through the binary32
+    # output transform: within its rounding of the oracle's binary64 evaluation, element by element.
+    points = synth.point_set(name, m)
+    t = nova.nova_make_transforms(points, m, 3)
+    x, w = synth.make_layer(N, C, K, H, W, seed=700 + m + C, dtype=dtype, x_dist="normal")
+    xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+    x64, w64 = x.astype(np.float64), w.astype(np.float64)
+    storage = 16 if dtype == "f16" else 32
+    n2 = t.n * t.n
+    T = N * (-(-H // m)) * (-(-W // m))
+    Tp, Kp = -(-T // 128) * 128, -(-K // 32) * 32
+    U = nova.nova_filter_transform(t, wd)
+    V = nova.nova_input_transform(t, xd)
+    A = np.abs(ct.to_f32(ct.cook_toom(pts(points), m, 3)[0]).astype(np.float64))
+    th, tw = -(-H // m), -(-W // m)
+    for mode, mode_name in ((nova.NOVA_INT8_PER_TENSOR, "per_tensor"), (nova.NOVA_INT8_PER_CHANNEL, "per_channel"),
+                            (nova.NOVA_INT8_PER_POSITION, "per_position")):
+        say(f"[case] int8 {mode_name} {name} F({m},3) {dtype} N={N} C={C} K={K} H={H} W={W}")
+        y_o, Uq_o, su_o, Vq_o, sv_o, Mi_o, M_o = int8.winograd_conv2d_int8(x64, w64, pts(points), m, storage=storage,
+                                                                         mode=mode_name, want_intermediates=True)
+        Uq, su = nova.nova_quantize_filter_int8(t, U, K, C, mode)
+        Vq, sv = nova.nova_quantize_input_int8(t, V, N, C, H, W, mode)
+        Mi = nova.nova_contract_int8(t, Uq, Vq, None, None, mode, N, C, H, W, K, dequantise=False)
+        Mf = nova.nova_contract_int8(t, Uq, Vq, su, sv, mode, N, C, H, W, K, dequantise=True)
+        y = nova.nova_output_transform(t, Mf, N, K, H, W, xd.dtype)
+        y2 = nova.nova_winograd_conv2d_int8(t, xd, Uq, su, mode, K)
+        torch.cuda.synchronize()
+        assert np.array_equal(su.cpu().numpy(), su_o) and np.array_equal(sv.cpu().numpy(), sv_o)
+        Uq_l = unblock(Uq, n2, Kp, C)
+        assert not Uq_l[:, K:, :].any()
+        same(Uq_l[:, :K, :], Uq_o.astype(np.float64), "Uq")
+        same(unblock(Vq, n2, T, C), Vq_o.astype(np.float64), "Vq")
+        same(unblock(Mi, n2, Tp, K)[:, :T, :], Mi_o.astype(np.float64), "Mi")
+        same(unblock(Mf, n2, Tp, K)[:, :T, :], M_o.astype(np.float64), "M (de-quantised)")
+        assert torch.equal(y, y2)
+        got = y.cpu().numpy().astype(np.float64)
+        # |y_gpu - y_oracle| <= rounding of the storage format + (2 n + 2) u |A|^T |M| |A|, u = 2^-24
+        S = np.einsum("ip,jq,ijtk->tkpq", A, A, np.abs(M_o.astype(np.float64)).reshape(t.n, t.n, T, K), optimize=True)
+        S = S.reshape(N, th, tw, K, m, m).transpose(0, 3, 1, 4, 2, 5).reshape(N, K, th * m, tw * m)[:, :, :H, :W]
+        spacing = ulp16(np.maximum(np.abs(got), np.abs(y_o))) if storage == 16 else 2.0 ** -23 * np.maximum(np.abs(got), np.abs(y_o))
+        bound = spacing + (2 * t.n + 2) * 2.0 ** -24 * S
+        assert np.isfinite(got).all() and (np.abs(got - y_o) <= bound).all(), float((np.abs(got - y_o) / bound).max())
+        want = conv.direct_conv2d(x64, w64)
+        say(f"  bit-exact codes, scales, sums; y: max |diff| / bound {float((np.abs(got - y_o) / bound).max()):.3f}; "
+            f"rel-L2 vs fp64 definition {rel_l2(got, want):.3e}")
+
+
+def test_int8_single_call_flags_and_errors():
+    m = 4
+    points = synth.point_set("nova", m)
+    t = nova.nova_make_transforms(points, m, 3)
+    x, w = synth.make_layer(2, 24, 40, 18, 20, seed=77, dtype="f16", x_dist="normal")
+    xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+    U = nova.nova_filter_transform(t, wd)
+    Uq, su = nova.nova_quantize_filter_int8(t, U, 40, 24, nova.NOVA_INT8_PER_CHANNEL)
+    y = nova.nova_winograd_conv2d_int8(t, xd, Uq, su, nova.NOVA_INT8_PER_CHANNEL, 40)
+    y_relu = nova.nova_winograd_conv2d_int8(t, xd, Uq, su, nova.NOVA_INT8_PER_CHANNEL, 40, flags=nova.NOVA_FLAG_RELU)
+    y_pool = nova.nova_winograd_conv2d_int8(t, xd, Uq, su, nova.NOVA_INT8_PER_CHANNEL, 40,
+                                            flags=nova.NOVA_FLAG_RELU | nova.NOVA_FLAG_POOL2)
+    assert torch.equal(y_relu, torch.clamp(y, min=0))
+    assert torch.equal(y_pool.float(), torch.nn.functional.max_pool2d(y_relu.float(), 2))
+    with pytest.raises(nova.NovaError) as exc:
+        nova.nova_winograd_conv2d_int8(t, xd, Uq, su, nova.NOVA_INT8_PER_CHANNEL, 40, flags=nova.NOVA_FLAG_M_F16)
+    assert exc.value.code == -1
+    small = torch.empty(nova.nova_conv2d_int8_workspace_bytes(2, 24, 18, 20, 40, m, nova.NOVA_F16) - 256,
+                        dtype=torch.uint8, device=DEV)
+    with pytest.raises(nova.NovaError) as exc:
+        nova.nova_winograd_conv2d_int8(t, xd, Uq, su, nova.NOVA_INT8_PER_CHANNEL, 40, workspace=small)
+    assert exc.value.code == -5
+    with pytest.raises(nova.NovaError) as exc:
+        nova.nova_quantize_filter_int8(t, U, 40, 24, 7)
+    assert exc.value.code == -1
+    torch.cuda.synchronize()
 
 
 POISON_CASES = [
