@@ -148,6 +148,37 @@ void nova_free_transforms(nova_transforms *t);
 int nova_symmetric_search(int m, int r, int d_max, nova_rational *points_out, double *kappa_out);
 int nova_snap_to_rational(double x, int d_max, nova_rational *out);
 
+/*
+ * The evolution strategy over R^(n-1) (Sec. "Evolution Strategy"; Alg. "Evolution Strategy for Winograd
+ * Point Discovery"; Tables "Evolution Strategy hyperparameters" and "Fitness function weights"), host only.
+ *
+ * nova_es_fitness: f(p) = || T - T_rec(p) ||_F + 0.001 |p|^2 / (n - 1) + 0.0001 log10(kappa(V) + 1) for n - 1
+ *   finite points given as doubles, T_rec the tensor rebuilt from the Cook-Toom matrices of p evaluated
+ *   in binary64; parts_out (may be NULL): tensor error, |p|^2 / (n - 1), kappa(V).  +infinity when a part
+ *   is not finite (coinciding points).
+ * nova_evolution_strategy: `restarts` independent runs of `generations` generations with `population`
+ *   candidates each: mean mu ~ N(0, 0.5 I), step sigma = 0.5; every generation samples mu + sigma eps,
+ *   moves mu to the mean of the best quarter, multiplies sigma by 1.1 if more than 20 % of the
+ *   candidates are fitter than the mean they were sampled around, else by 0.9 (kept within
+ *   [0.01, 2]); the fittest candidate ever seen is returned (points_out: n - 1 doubles).
+ *   The random numbers are an argument: `normals` holds at least nova_es_normals_needed(..)
+ *   independent standard normal draws, consumed in order (per restart n - 1 for mu, then per generation
+ *   population * (n - 1), candidate by candidate), so a run is a function of its arguments.
+ *   The paper's values: generations 100, population 50, restarts 3.
+ * nova_snap_points: the step after it (Sec. "Snap-to-Rational", "Neighborhood Search"): every coordinate
+ *   to its nearest simple fraction (nova_snap_to_rational); if two coincide, each point gets the
+ *   fractions within 6/5 of its snapped value, nearest to its continuous value first -- as many per
+ *   point as keep the combinations within 1e5 -- and the combination of distinct points with the
+ *   lowest kappa(V) wins (the first one enumerated, last point varying fastest, among those within a
+ *   relative 1e-9 of each other); the result is verified exactly.  points_out: n - 1 entries in the order of x.
+ * Errors: NOVA_EINVAL; NOVA_EVERIFY if no candidate was ever valid.
+ */
+int nova_es_fitness(int m, int r, const double *points, double *fitness_out, double parts_out[3]);
+size_t nova_es_normals_needed(int m, int r, int generations, int population, int restarts);
+int nova_evolution_strategy(int m, int r, int generations, int population, int restarts,
+                            const double *normals, size_t n_normals, double *points_out, double *fitness_out);
+int nova_snap_points(int m, int r, const double *x, int d_max, nova_rational *points_out, double *kappa_out);
+
 /* m, r, n of a handle; `symmetric` = 1 when the points come as 0, +a1, -a1, +a2, -a2, ...
  * (the order for which the device transforms share work between +a and -a). Any pointer may be NULL. */
 int nova_transforms_shape(const nova_transforms *t, int *m, int *r, int *n, int *symmetric);

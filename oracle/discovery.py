@@ -84,3 +84,148 @@ def snap_to_rational(x, d_max=10, bound=5):
             if best is None or dist < best_dist:
                 best, best_dist = f, dist
     return best
+
+
+# ---------------------------------------------------------------------------------------------
+# Evolution strategy (Sec. "Evolution Strategy", Alg. "Evolution Strategy for Winograd Point
+# Discovery", Table "Evolution Strategy hyperparameters", Table "Fitness function weights").
+#
+# The random numbers are an input: `normals` is a sequence of independent standard normal draws
+# that is consumed in the order the algorithm needs them (per restart: n - 1 for the initial mean,
+# then per generation population * (n - 1) for the offspring, candidate by candidate).
+#
+# Readings where the text leaves a choice: mu ~ N(0, 0.5 I) is taken as covariance 0.5 I (standard
+# deviation sqrt(0.5)); the "success rate" of the 1/5 rule is the fraction of offspring that are
+# fitter than the mean they were sampled around; the elite is the best floor(0.25 * population)
+# (at least one), ties in fitness broken by sample index; sigma is clamped to [0.01, 2.0] after
+# every adaptation; a configuration whose fitness is not finite (coinciding points) ranks last.
+
+ES_LAMBDA_MAGNITUDE = 1e-3
+ES_LAMBDA_CONDITION = 1e-4
+
+
+def float_cook_toom(p, m, r):
+    """A (n x m), B^T (n x n), G (n x r) from finite points given as floats, in binary64: the
+    construction of cook_toom.cook_toom with every operation rounded."""
+    n = m + r - 1
+    p = [float(v) for v in p]
+    assert len(p) == n - 1
+    A = np.zeros((n, m))
+    BT = np.zeros((n, n))
+    G = np.zeros((n, r))
+    full = [1.0]                                   # coefficients of prod_j (t - p_j), ascending
+    for j in range(n - 1):
+        full = [(full[k - 1] if k > 0 else 0.0) - p[j] * (full[k] if k < len(full) else 0.0) for k in range(len(full) + 1)]
+    for q in range(n - 1):
+        lag = [1.0]                                # coefficients of prod_{j != q} (t - p_j)
+        f = 1.0
+        for j in range(n - 1):
+            if j == q:
+                continue
+            lag = [(lag[k - 1] if k > 0 else 0.0) - p[j] * (lag[k] if k < len(lag) else 0.0) for k in range(len(lag) + 1)]
+            f *= p[q] - p[j]
+        BT[q, :n - 1] = lag
+        pw = 1.0
+        for i in range(max(m, r)):
+            if i < m:
+                A[q, i] = pw
+            if i < r:
+                G[q, i] = pw / f if f != 0.0 else np.inf
+            pw *= p[q]
+    A[n - 1, m - 1] = 1.0
+    G[n - 1, r - 1] = 1.0
+    BT[n - 1, :] = full
+    return A, BT, G
+
+
+def es_fitness(p, m, r=3):
+    """f(p) = tensor error + 0.001 |p|^2 / (n - 1) + 0.0001 log10(kappa(V) + 1)  (Sec. "Evolution
+    Strategy", "Fitness Function").  Returns (f, tensor error, magnitude term, kappa)."""
+    n = m + r - 1
+    with np.errstate(all="ignore"):
+        A, BT, G = float_cook_toom(p, m, r)
+        rec = np.einsum("qi,qj,qk->ijk", A, BT, G)
+        target = np.zeros((m, n, r))
+        for i in range(m):
+            for k in range(r):
+                target[i, i + k, k] = 1.0
+        err = float(np.sqrt(np.sum((rec - target) ** 2)))
+        mag = float(sum(float(v) ** 2 for v in p) / (n - 1))
+        vander = np.array([[float(v) ** j for j in range(n - 1)] for v in p])
+        sv = np.linalg.svd(vander, compute_uv=False)
+        kappa = float(sv[0] / sv[-1]) if sv[-1] > 0 else np.inf
+        f = err + ES_LAMBDA_MAGNITUDE * mag + ES_LAMBDA_CONDITION * np.log10(kappa + 1.0)
+    if not np.isfinite(f):
+        f = np.inf
+    return float(f), err, mag, kappa
+
+
+def es_normals_needed(m, r=3, generations=100, population=50, restarts=3):
+    return restarts * (m + r - 2) * (1 + generations * population)
+
+
+def evolution_strategy(m, r, normals, generations=100, population=50, restarts=3):
+    """Alg. "Evolution Strategy for Winograd Point Discovery".  Returns (best points, best fitness)."""
+    dim = m + r - 2
+    z = iter(np.asarray(normals, dtype=np.float64).tolist())
+    elite_count = max(1, population // 4)
+    best_p, best_f = None, np.inf
+    for _ in range(restarts):
+        mu = [np.sqrt(0.5) * next(z) for _ in range(dim)]
+        sigma = 0.5
+        for _ in range(generations):
+            f_parent = es_fitness(mu, m, r)[0]
+            cands = [[mu[d] + sigma * next(z) for d in range(dim)] for _ in range(population)]
+            fits = [es_fitness(c, m, r)[0] for c in cands]
+            order = sorted(range(population), key=lambda i: (fits[i], i))
+            elite = order[:elite_count]
+            new_mu = []
+            for d in range(dim):
+                acc = 0.0
+                for i in elite:
+                    acc += cands[i][d]
+                new_mu.append(acc / elite_count)
+            mu = new_mu
+            success = sum(1 for v in fits if v < f_parent) / population
+            sigma = sigma * 1.1 if success > 0.2 else sigma * 0.9
+            sigma = min(2.0, max(0.01, sigma))
+            if fits[order[0]] < best_f:
+                best_f, best_p = fits[order[0]], list(cands[order[0]])
+    return best_p, best_f
+
+
+def snap_points(x, m, r=3, d_max=10, bound=5, radius=Fraction(6, 5), budget=10 ** 5):
+    """Sec. "Snap-to-Rational" and "Neighborhood Search": every coordinate goes to its nearest simple
+    fraction; if two of them coincide (the one way a set of points can be invalid), every point gets
+    the candidates a/b (b <= d_max, |a| <= bound * b) within `radius` of its snapped value, nearest to
+    its continuous value first -- as many per point as keep the number of combinations within
+    `budget` (a deterministic stand-in for the sampling the text mentions) -- and the combination of
+    distinct points with the lowest kappa(V) wins (first in enumeration order, last point varying
+    fastest, among those within a relative 1e-9 of each other).
+    The result is verified exactly.  Returns (points as Fractions, kappa)."""
+    dim = m + r - 2
+    assert len(x) == dim
+    snapped = [snap_to_rational(v, d_max, bound) for v in x]
+    points = snapped
+    if len(set(snapped)) < dim:
+        per_point = max(1, int(np.floor(budget ** (1.0 / dim) + 1e-9)))
+        every = sorted({Fraction(a, b) for b in range(1, d_max + 1) for a in range(-bound * b, bound * b + 1)})
+        choices = []
+        for v, s in zip(x, snapped):
+            near = [c for c in every if abs(c - s) <= radius]
+            near.sort(key=lambda c: (abs(c - Fraction(v)), c))
+            choices.append(near[:per_point])
+        best, best_kappa = None, np.inf
+        for combo in itertools.product(*choices):
+            if len(set(combo)) < dim:
+                continue
+            kappa = ct.kappa_V(list(combo))
+            if kappa < best_kappa * (1.0 - 1e-9):      # (permutations of one set differ in the last bits only)
+                best, best_kappa = list(combo), kappa
+        if best is None:
+            raise ValueError("no valid configuration near the snapped points")
+        points = best
+    A, BT, G = ct.cook_toom(points, m, r)
+    if not ct.tensor_identity_holds(A, BT, G):
+        raise AssertionError("symbolic verification failed")
+    return points, ct.kappa_V(points)

@@ -26,6 +26,7 @@ EXPORTS = [
     "nova_get_matrix_f64", "nova_get_matrix_f32", "nova_kappa", "nova_filter_bytes", "nova_input_bytes",
     "nova_product_bytes", "nova_filter_transform", "nova_conv2d_workspace_bytes", "nova_winograd_conv2d",
     "nova_winograd_conv2d_static", "nova_static_workspace_bytes",
+    "nova_es_fitness", "nova_es_normals_needed", "nova_evolution_strategy", "nova_snap_points",
     "nova_filter_int8_bytes", "nova_input_int8_bytes", "nova_quantize_filter_int8", "nova_quantize_input_int8",
     "nova_contract_int8", "nova_conv2d_int8_workspace_bytes", "nova_winograd_conv2d_int8",
     "nova_input_transform", "nova_contract", "nova_output_transform", "nova_relu_maxpool2x2",
@@ -62,6 +63,12 @@ def lib():
         L.nova_free_transforms.argtypes = [vp]
         L.nova_symmetric_search.argtypes = [i, i, i, ctypes.POINTER(nova_rational), ctypes.POINTER(ctypes.c_double)]
         L.nova_snap_to_rational.argtypes = [ctypes.c_double, i, ctypes.POINTER(nova_rational)]
+        dp = ctypes.POINTER(ctypes.c_double)
+        L.nova_es_fitness.argtypes = [i, i, dp, dp, dp]
+        L.nova_es_normals_needed.argtypes = [i] * 5
+        L.nova_es_normals_needed.restype = sz
+        L.nova_evolution_strategy.argtypes = [i, i, i, i, i, dp, sz, dp, dp]
+        L.nova_snap_points.argtypes = [i, i, dp, i, ctypes.POINTER(nova_rational), dp]
         L.nova_free_transforms.restype = None
         L.nova_transforms_shape.argtypes = [vp, ip, ip, ip, ip]
         L.nova_get_matrix.argtypes = [vp, i, ctypes.POINTER(nova_rational)]
@@ -191,6 +198,36 @@ def nova_snap_to_rational(x, d_max=10):
     out = nova_rational()
     _check(lib().nova_snap_to_rational(float(x), d_max, ctypes.byref(out)), "nova_snap_to_rational")
     return Fraction(out.num, out.den)
+
+
+def nova_es_fitness(m, r, points):
+    """(f, tensor error, |p|^2 / (n - 1), kappa(V)) of finite points given as floats."""
+    pts = (ctypes.c_double * len(points))(*[float(v) for v in points])
+    f, parts = ctypes.c_double(), (ctypes.c_double * 3)()
+    _check(lib().nova_es_fitness(m, r, pts, ctypes.byref(f), parts), "nova_es_fitness")
+    return f.value, parts[0], parts[1], parts[2]
+
+
+def nova_es_normals_needed(m, r=3, generations=100, population=50, restarts=3):
+    return int(lib().nova_es_normals_needed(m, r, generations, population, restarts))
+
+
+def nova_evolution_strategy(m, r, normals, generations=100, population=50, restarts=3):
+    """normals: sequence of standard normal draws (at least nova_es_normals_needed).  -> (points, fitness)."""
+    z = (ctypes.c_double * len(normals))(*[float(v) for v in normals])
+    out = (ctypes.c_double * (m + r - 2))()
+    f = ctypes.c_double()
+    _check(lib().nova_evolution_strategy(m, r, generations, population, restarts, z, len(normals), out, ctypes.byref(f)),
+           "nova_evolution_strategy")
+    return list(out), f.value
+
+
+def nova_snap_points(m, r, x, d_max=10):
+    pts = (ctypes.c_double * len(x))(*[float(v) for v in x])
+    out = (nova_rational * (m + r - 2))()
+    kappa = ctypes.c_double()
+    _check(lib().nova_snap_points(m, r, pts, d_max, out, ctypes.byref(kappa)), "nova_snap_points")
+    return [Fraction(p.num, p.den) for p in out], kappa.value
 
 
 def nova_get_row_scaling(t):

@@ -239,3 +239,35 @@ def test_snap_to_rational_equals_oracle():
     assert L.nova_snap_to_rational(float("nan"), 10, ctypes.byref(out)) == -1
     assert L.nova_snap_to_rational(0.5, 0, ctypes.byref(out)) == -1
     assert L.nova_snap_to_rational(0.5, 10, None) == -1
+
+
+def test_evolution_strategy_equals_oracle_for_fixed_draws():
+    # Alg. "Evolution Strategy for Winograd Point Discovery": the same standard normal draws go to both
+    # implementations; fitness values agree to rounding and the runs pick the same candidates
+    from oracle import discovery
+    for m in (2, 4, 6):
+        p = [a / b for a, b in synth.NOVA[m]]
+        got, want = nova.nova_es_fitness(m, 3, p), discovery.es_fitness(p, m, 3)
+        assert got[0] == pytest.approx(want[0], rel=1e-12) and got[3] == pytest.approx(want[3], rel=1e-10)
+        assert got[1] < 1e-12 and got[2] == pytest.approx(want[2], rel=1e-15)
+    assert nova.nova_es_fitness(4, 3, [0.5, 0.5, 1.0, -1.0, 0.0])[0] == np.inf
+    for m, seed, gens, pop, restarts in ((4, 0, 12, 20, 2), (6, 1, 6, 16, 1), (2, 2, 10, 8, 3)):
+        count = discovery.es_normals_needed(m, 3, gens, pop, restarts)
+        assert nova.nova_es_normals_needed(m, 3, gens, pop, restarts) == count
+        z = np.random.default_rng(seed).standard_normal(count)
+        p_o, f_o = discovery.evolution_strategy(m, 3, z, gens, pop, restarts)
+        p_l, f_l = nova.nova_evolution_strategy(m, 3, z, gens, pop, restarts)
+        assert f_l == pytest.approx(f_o, rel=1e-9)
+        assert np.allclose(p_l, p_o, rtol=0, atol=1e-9)
+    with pytest.raises(nova.NovaError):
+        nova.nova_evolution_strategy(4, 3, np.zeros(10), 12, 20, 2)          # too few draws
+
+
+def test_snap_points_equals_oracle():
+    from oracle import discovery
+    for x in ([0.0, 0.8334, -0.8331, 1.1669, -1.16], [0.3301, 0.3302, -0.5, 0.0, 1.0], [0.04, -0.21, 0.35, 0.28, -0.36]):
+        want, kappa_o = discovery.snap_points(x, 4, 3)
+        got, kappa_l = nova.nova_snap_points(4, 3, x)
+        assert got == want and kappa_l == pytest.approx(kappa_o, rel=1e-10)
+    want, _ = discovery.snap_points([0.1, 0.1001, -0.7], 2, 3, d_max=4)
+    assert nova.nova_snap_points(2, 3, [0.1, 0.1001, -0.7], d_max=4)[0] == want
