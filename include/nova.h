@@ -326,6 +326,18 @@ int nova_winograd_conv2d_int8(const nova_transforms *t, const void *x, const voi
                               int mode, void *y, int N, int C, int H, int W, int K, int dtype, int flags,
                               void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Steps 3 and 4 (Sec. 2.1) in one kernel: y = A^T [ sum_c U * V ] A per tile and output channel, the
+ * products kept in registers and never written as M.  For layers with few input channels, where M is
+ * most of the memory traffic: NOVA_F16 storage, points in the order 0, +a, -a, .., F(6,3) or F(8,3),
+ * C = 64 or 128, K a multiple of 64, without NOVA_FLAG_M_F16; other requests: NOVA_EUNSUPPORTED.
+ * nova_winograd_conv2d takes this path by itself for such shapes (its result then differs from
+ * nova_contract + nova_output_transform by the summation order of the matrix unit only).
+ * U, V as for nova_contract; y, flags (ReLU, max-pool) as for nova_output_transform.
+ */
+int nova_contract_output_fused(const nova_transforms *t, const void *U, const void *V, void *y,
+                               int N, int C, int H, int W, int K, int dtype, int flags, void *stream);
+
 /* out = maxpool2x2(max(in, 0)), stride 2, floor; in [N][C][H][W] -> out [N][C][H/2][W/2] (device).
  * The step between the blocks of a VGG-style stack. */
 int nova_relu_maxpool2x2(const void *in, void *out, int N, int C, int H, int W, int dtype, void *stream);

@@ -18,7 +18,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnova.so")
 
 SOURCES = ["transforms.cpp", "discovery.cpp", "api.cpp", "filter_transform.hip", "input_transform.hip",
-           "contract.hip", "output_transform.hip", "pool.hip", "static_workspace.hip", "int8.hip"]
+           "contract.hip", "output_transform.hip", "pool.hip", "static_workspace.hip", "int8.hip", "fused_output.hip"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-Wno-unused-function"]
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -151,6 +151,17 @@ extern "C" int nova_output_transform(const nova_transforms *t, const void *M, si
     return hip_result(launch_output_transform(t, M, y, g, dtype, flags, stream));
 }
 
+extern "C" int nova_contract_output_fused(const nova_transforms *t, const void *U, const void *V, void *y, int N, int C,
+                                          int H, int W, int K, int dtype, int flags, void *stream)
+{
+    if (int rc = check_handle(t)) return rc;
+    if (!U || !V || !y || !dims_ok(N, C, H, W, K) || !dtype_ok(dtype)) return NOVA_EINVAL;
+    if ((flags & NOVA_FLAG_POOL2) && (H % 2 != 0 || W % 2 != 0)) return NOVA_EINVAL;
+    const Geometry g = make_geometry(N, C, H, W, K, t->m, t->r);
+    if (!fused_contract_output_applies(t, g, dtype, flags)) return NOVA_EUNSUPPORTED;
+    return hip_result(launch_fused_contract_output(t, U, V, y, g, dtype, flags, stream));
+}
+
 // The slab loop behind nova_winograd_conv2d and nova_winograd_conv2d_static.
 int nova::conv2d_with_workspace(const nova_transforms *t, const void *x, const void *U, void *y, int N,
                                 int C, int H, int W, int K, int dtype, int flags, void *workspace,
@@ -162,12 +173,14 @@ int nova::conv2d_with_workspace(const nova_transforms *t, const void *x, const v
     if ((flags & NOVA_FLAG_POOL2) && (H % 2 != 0 || W % 2 != 0)) return NOVA_EINVAL;
     const int m = t->m, r = t->r;
 
+    // (few input channels at large K: contraction and output transform run as one kernel and keep no M)
+    const bool fused = fused_contract_output_applies(t, make_geometry(1, C, H, W, K, m, r), dtype, flags);
     // largest slab (whole images) whose V and M fit the workspace; slab_bytes grows with the count
     auto slab_bytes = [&](long long count, size_t *v_part) {
         const Geometry sg = make_geometry((int)count, C, H, W, K, m, r);
         const size_t vb = align256(first_part_bytes(sg, dtype));
         if (v_part) *v_part = vb;
-        return vb + align256(second_part_bytes(sg, dtype, flags));
+        return vb + (fused ? 0 : align256(second_part_bytes(sg, dtype, flags)));
     };
     if (slab_bytes(1, nullptr) > workspace_bytes) return NOVA_ENOSPC;
     long long lo = 1, hi = N;                    // invariant: lo fits
@@ -199,6 +212,10 @@ int nova::conv2d_with_workspace(const nova_transforms *t, const void *x, const v
             continue;
         }
         if (int err = launch_input_transform(t, xs, Vbuf, g, dtype, stream)) return hip_result(err);
+        if (fused) {
+            if (int err = launch_fused_contract_output(t, U, Vbuf, ys, g, dtype, flags, stream)) return hip_result(err);
+            continue;
+        }
         if (int err = launch_contract(t, U, Vbuf, Mbuf, g, dtype, flags, stream)) return hip_result(err);
         if (int err = launch_output_transform(t, Mbuf, ys, g, dtype, flags, stream)) return hip_result(err);
     }

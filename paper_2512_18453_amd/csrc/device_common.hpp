@@ -96,17 +96,57 @@ __device__ __forceinline__ void global_to_lds16(const void *uniform_base, unsign
                      : "=&s"(saved_m0) : "s"(lds_wave_base), "v"(byte_offset), "s"(uniform_base) : "memory");
 }
 
+// COUNT such loads in one statement (M0 saved and handed back once): load k takes the 64 pieces at
+// planes[k] + byte_offset to LDS at lds_wave_base + k * LDS_STEP.
+#define NOVA_DMA_FIRST "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %4\n\t"
+#define NOVA_DMA_NEXT(P) "s_add_u32 m0, m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, " P "\n\t"
+#define NOVA_DMA_LAST "s_mov_b32 m0, %0"
+template <int COUNT, int LDS_STEP>
+__device__ __forceinline__ void global_to_lds16_run(const void *const (&planes)[COUNT], unsigned byte_offset, unsigned lds_wave_base)
+{
+    static_assert(COUNT >= 1 && COUNT <= 5, "loads per statement");
+    unsigned saved_m0;
+    if constexpr (COUNT == 1)
+        asm volatile(NOVA_DMA_FIRST NOVA_DMA_LAST
+                     : "=&s"(saved_m0) : "s"(lds_wave_base), "v"(byte_offset), "n"(LDS_STEP), "s"(planes[0]) : "memory", "scc");
+    else if constexpr (COUNT == 2)
+        asm volatile(NOVA_DMA_FIRST NOVA_DMA_NEXT("%5") NOVA_DMA_LAST
+                     : "=&s"(saved_m0) : "s"(lds_wave_base), "v"(byte_offset), "n"(LDS_STEP), "s"(planes[0]), "s"(planes[1])
+                     : "memory", "scc");
+    else if constexpr (COUNT == 3)
+        asm volatile(NOVA_DMA_FIRST NOVA_DMA_NEXT("%5") NOVA_DMA_NEXT("%6") NOVA_DMA_LAST
+                     : "=&s"(saved_m0)
+                     : "s"(lds_wave_base), "v"(byte_offset), "n"(LDS_STEP), "s"(planes[0]), "s"(planes[1]), "s"(planes[2])
+                     : "memory", "scc");
+    else if constexpr (COUNT == 4)
+        asm volatile(NOVA_DMA_FIRST NOVA_DMA_NEXT("%5") NOVA_DMA_NEXT("%6") NOVA_DMA_NEXT("%7") NOVA_DMA_LAST
+                     : "=&s"(saved_m0)
+                     : "s"(lds_wave_base), "v"(byte_offset), "n"(LDS_STEP), "s"(planes[0]), "s"(planes[1]), "s"(planes[2]),
+                       "s"(planes[3])
+                     : "memory", "scc");
+    else
+        asm volatile(NOVA_DMA_FIRST NOVA_DMA_NEXT("%5") NOVA_DMA_NEXT("%6") NOVA_DMA_NEXT("%7") NOVA_DMA_NEXT("%8") NOVA_DMA_LAST
+                     : "=&s"(saved_m0)
+                     : "s"(lds_wave_base), "v"(byte_offset), "n"(LDS_STEP), "s"(planes[0]), "s"(planes[1]), "s"(planes[2]),
+                       "s"(planes[3]), "s"(planes[4])
+                     : "memory", "scc");
+}
+#undef NOVA_DMA_FIRST
+#undef NOVA_DMA_NEXT
+#undef NOVA_DMA_LAST
+
 // s_waitcnt vmcnt(n) for a wave-uniform run-time n: waits until at most min(n, 31) of the wave's
 // vector-memory operations are outstanding (the count is an immediate of the instruction, hence the
-// ladder; waiting for fewer than n is always safe).
-template <int LIMIT = 31>
+// decision tree: five comparisons; waiting for fewer than n is always safe).
+template <int LO = 0, int HI = 31>
 __device__ __forceinline__ void wait_vmcnt_at_most(int n)
 {
-    if constexpr (LIMIT == 0) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if constexpr (LO == HI) {
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(LO) : "memory");
     } else {
-        if (n >= LIMIT) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(LIMIT) : "memory");
-        else wait_vmcnt_at_most<LIMIT - 1>(n);
+        constexpr int MID = (LO + HI + 1) / 2;
+        if (n >= MID) wait_vmcnt_at_most<MID, HI>(n);
+        else wait_vmcnt_at_most<LO, MID - 1>(n);
     }
 }
 

@@ -26,7 +26,7 @@ EXPORTS = [
     "nova_get_matrix_f64", "nova_get_matrix_f32", "nova_kappa", "nova_filter_bytes", "nova_input_bytes",
     "nova_product_bytes", "nova_filter_transform", "nova_conv2d_workspace_bytes", "nova_winograd_conv2d",
     "nova_winograd_conv2d_static", "nova_static_workspace_bytes",
-    "nova_es_fitness", "nova_es_normals_needed", "nova_evolution_strategy", "nova_snap_points",
+    "nova_contract_output_fused", "nova_es_fitness", "nova_es_normals_needed", "nova_evolution_strategy", "nova_snap_points",
     "nova_filter_int8_bytes", "nova_input_int8_bytes", "nova_quantize_filter_int8", "nova_quantize_input_int8",
     "nova_contract_int8", "nova_conv2d_int8_workspace_bytes", "nova_winograd_conv2d_int8",
     "nova_input_transform", "nova_contract", "nova_output_transform", "nova_relu_maxpool2x2",
@@ -98,6 +98,7 @@ def lib():
         L.nova_conv2d_int8_workspace_bytes.argtypes = [i] * 8
         L.nova_conv2d_int8_workspace_bytes.restype = sz
         L.nova_winograd_conv2d_int8.argtypes = [vp, vp, vp, vp, i, vp, i, i, i, i, i, i, i, vp, sz, vp]
+        L.nova_contract_output_fused.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
         L.nova_input_transform.argtypes = [vp, vp, vp, sz, i, i, i, i, i, vp]
         L.nova_contract.argtypes = [vp, vp, vp, vp, sz, i, i, i, i, i, i, i, vp]
         L.nova_output_transform.argtypes = [vp, vp, sz, vp, i, i, i, i, i, i, vp]
@@ -409,6 +410,15 @@ def nova_winograd_conv2d_int8(t, x, Uq, u_scales, mode, K, y=None, flags=0, work
     _check(lib().nova_winograd_conv2d_int8(t.handle, _dev(x), _dev(Uq), _dev(u_scales), mode, _dev(y), N, C, H, W, K, dt,
                                            flags, _dev(workspace), workspace.numel(), _stream()),
            "nova_winograd_conv2d_int8")
+    return y
+
+
+def nova_contract_output_fused(t, U, V, N, C, H, W, K, flags=0, y=None):
+    if y is None:
+        out_hw = (H // 2, W // 2) if flags & NOVA_FLAG_POOL2 else (H, W)
+        y = torch.empty((N, K) + out_hw, dtype=V.dtype, device=V.device)
+    _check(lib().nova_contract_output_fused(t.handle, _dev(U), _dev(V), _dev(y), N, C, H, W, K, _dtype_code(V), flags,
+                                            _stream()), "nova_contract_output_fused")
     return y
 
 

@@ -109,14 +109,26 @@ def same(got, want, what):
     raise AssertionError("\n".join(lines))
 
 
-def single_call_agrees(got, C, storage):
+def takes_fused_path(t, C, K, dtype, flags=0):
+    """Shapes for which nova_winograd_conv2d runs contraction and output transform as one kernel."""
+    return (dtype == np.float16 and not flags & nova.NOVA_FLAG_M_F16 and t.symmetric and t.r == 3 and t.n in (8, 10)
+            and C == 64 and K % 64 == 0)
+
+
+def single_call_agrees(got, C, storage, fused=False):
     """nova_winograd_conv2d against the three stage calls.  They run the same kernels, so the results
     are equal bit for bit -- except with at most 4 input channels, where the single call forms the
     products inside the output transform (a binary32 multiply-add chain over the channels instead of
     the matrix unit's summation order): then the two agree to rounding."""
     a, b = got["y"], got["y_conv"]
-    if C > 4:
+    if C > 4 and not fused:
         assert np.array_equal(a, b, equal_nan=True)
+        return
+    if fused:
+        # one kernel instead of two: another shape of matrix instruction, hence another summation order
+        # over the channels; the callers check the single call's result against the emulation element by
+        # element, here only that the two are close
+        assert np.array_equal(np.isfinite(a), np.isfinite(b)) and rel_l2(a, b) < 1e-3
         return
     fin = np.isfinite(a) & np.isfinite(b)
     assert (np.isfinite(a) == np.isfinite(b)).mean() > 0.99
@@ -146,12 +158,13 @@ def run_stages(t, x, w, flags=0):
     y = nova.nova_output_transform(t, M, N, K, H, W, xd.dtype, flags)
     y2 = nova.nova_winograd_conv2d(t, xd, U, K, flags=flags, images_per_slab=1)
     torch.cuda.synchronize()
+    fused = takes_fused_path(t, C, K, x.dtype, flags)
     Kp = -(-K // 32) * 32
     Ul = unblock(U, n2, Kp, C)
     assert not Ul[:, K:, :].any()                       # padding rows are zero
     Tp = -(-T // 128) * 128                             # M has Tp rows per block; rows >= T are scratch
     out = dict(U=Ul[:, :K, :], V=unblock(V, n2, T, C), M=unblock(M, n2, Tp, K)[:, :T, :],
-               y=y.cpu().numpy().astype(np.float64), y_conv=y2.cpu().numpy().astype(np.float64))
+               y=y.cpu().numpy().astype(np.float64), y_conv=y2.cpu().numpy().astype(np.float64), fused=fused)
     return out
 
 
@@ -197,7 +210,7 @@ def test_fp16_stages_against_emulation(name, m, N, C, K, H, W):
     same(got["U"], U_o, "U")
     same(got["V"], V_o, "V")
     assert rel_l2(got["M"], M_o) < 1e-5
-    single_call_agrees(got, x.shape[1], 16 if x.dtype == np.float16 else 32)
+    single_call_agrees(got, x.shape[1], 16 if x.dtype == np.float16 else 32, got["fused"])
     err = rel_l2(got["y"], y_o)
     say(f"  rel-L2 vs emulation {err:.3e}; vs fp64 definition {rel_l2(got['y'], conv.direct_conv2d(x64, w64)):.3e}")
     assert err < 5e-3
@@ -218,7 +231,7 @@ def test_fp32_small_layer_against_definition():
     err, mx = rel_l2(got["y"], want), float(np.abs(got["y"] - want).max())
     say(f"  rel-L2 {err:.3e} max-abs {mx:.3e}")
     assert err <= 1e-5 and mx <= 1e-4
-    single_call_agrees(got, x.shape[1], 16 if x.dtype == np.float16 else 32)
+    single_call_agrees(got, x.shape[1], 16 if x.dtype == np.float16 else 32, got["fused"])
     _, U_o, V_o, _ = conv.winograd_conv2d_emulated(x.astype(np.float64), w.astype(np.float64), pts(points), 4,
                                                    storage=32, want_intermediates=True)
     same(got["U"], U_o, "U")
@@ -259,7 +272,7 @@ def test_fp32_narrow_images(m):
     err = rel_l2(got["y"], y_o)
     say(f"  emulation vs definition {own:.3e}; gpu vs emulation {err:.3e}")
     assert err <= max(1e-5, 4 * own)
-    single_call_agrees(got, x.shape[1], 16 if x.dtype == np.float16 else 32)
+    single_call_agrees(got, x.shape[1], 16 if x.dtype == np.float16 else 32, got["fused"])
 
 
 def test_generic_point_order_uses_the_same_contract():
@@ -722,7 +735,7 @@ def test_r5_fp16_stages_against_emulation(m, pset, N, C, K, H, W):
     same(got["U"], U_o, "U")
     same(got["V"], V_o, "V")
     assert rel_l2(got["M"], M_o) < 1e-5
-    single_call_agrees(got, x.shape[1], 16 if x.dtype == np.float16 else 32)
+    single_call_agrees(got, x.shape[1], 16 if x.dtype == np.float16 else 32, got["fused"])
     err = rel_l2(got["y"], y_o)
     say(f"  rel-L2 vs emulation {err:.3e}; vs fp64 definition {rel_l2(got['y'], conv.direct_conv2d(x64, w64)):.3e}")
     assert err < 5e-3
@@ -748,6 +761,54 @@ def test_r5_fp32_against_definition(m, pset):
     assert err <= max(1e-5, 4 * own)
     if m == 2:
         assert rel_l2(got["y"], want) <= 1e-5 and np.abs(got["y"] - want).max() <= 1e-4
+
+
+FUSED_CASES = [
+    # m, N, C, K, H, W: wide rows (two groups of tiles), one group, narrow images (several tile rows per group),
+    # ragged edges, several groups of 64 output channels
+    (8, 2, 64, 64, 224, 224),
+    (8, 2, 64, 128, 112, 112),
+    (8, 3, 64, 128, 56, 56),
+    (8, 2, 64, 192, 50, 61),
+    (8, 5, 64, 64, 17, 23),
+    (8, 7, 64, 64, 9, 8),
+    (6, 2, 64, 128, 56, 56),
+    (6, 3, 64, 64, 45, 100),
+    (6, 2, 64, 64, 13, 13),
+]
+
+
+@pytest.mark.parametrize("m,N,C,K,H,W", FUSED_CASES)
+def test_fused_contraction_and_output_transform(m, N, C, K, H, W):
+    # steps 3 and 4 in one kernel (no M): against the emulation, element by element, with ReLU and the
+    # fused max-pool; and nova_winograd_conv2d takes this path for these shapes
+    say(f"[case] fused contraction + output transform F({m},3) N={N} C={C} K={K} H={H} W={W}")
+    points = synth.point_set("nova", m)
+    t = nova.nova_make_transforms(points, m, 3)
+    x, w = synth.make_layer(N, C, K, H, W, seed=800 + m + C + H, dtype="f16", x_dist="normal")
+    xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
+    U = nova.nova_filter_transform(t, wd)
+    V = nova.nova_input_transform(t, xd)
+    y = nova.nova_contract_output_fused(t, U, V, N, C, H, W, K)
+    y_relu = nova.nova_contract_output_fused(t, U, V, N, C, H, W, K, flags=nova.NOVA_FLAG_RELU)
+    y_call = nova.nova_winograd_conv2d(t, xd, U, K, images_per_slab=1)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_call)
+    assert torch.equal(y_relu, torch.clamp(y, min=0))
+    sample = [0, N - 1] if H * W > 10000 else list(range(N))
+    x64, w64 = x[sample].astype(np.float64), w.astype(np.float64)
+    emu = conv.winograd_conv2d_emulated(x64, w64, pts(points), m, storage=16, want_intermediates=True)
+    got = y[sample].cpu().numpy().astype(np.float64)
+    err = rel_l2(got, emu[0])
+    ratio, width = elementwise_fp16(got, emu[0], points, m, emu, C)
+    say(f"  rel-L2 vs emulation {err:.3e}; element-wise: max |diff| / bound {ratio:.3f}; median bound / rms(y) {width:.2e}")
+    assert err < 5e-3
+    if H % 2 == 0 and W % 2 == 0:
+        pooled = nova.nova_contract_output_fused(t, U, V, N, C, H, W, K, flags=nova.NOVA_FLAG_RELU | nova.NOVA_FLAG_POOL2)
+        assert torch.equal(pooled.float(), torch.nn.functional.max_pool2d(y_relu.float(), 2))
+    with pytest.raises(nova.NovaError) as exc:
+        nova.nova_contract_output_fused(t, U, V, N, C, H, W, K, flags=nova.NOVA_FLAG_M_F16)
+    assert exc.value.code == -6
 
 
 INT8_CASES = [
@@ -932,7 +993,7 @@ def test_degenerate_shapes(m, r):
                                                             want_intermediates=True)
             same(got["U"], U_o, "U")
             same(got["V"], V_o, "V")
-            single_call_agrees(got, x.shape[1], 16 if x.dtype == np.float16 else 32)
+            single_call_agrees(got, x.shape[1], 16 if x.dtype == np.float16 else 32, got["fused"])
             scale = max(np.abs(y_o).max(), 1e-30)
             assert np.abs(got["y"] - y_o).max() <= (4e-2 if storage == 16 else 1e-3) * scale
 
@@ -983,7 +1044,7 @@ def sweep_random_shapes(seed, count, max_hw=70, max_ch=70):
             m_storage=16 if flags & nova.NOVA_FLAG_M_F16 else 32, want_intermediates=True)
         same(got["U"], U_o, "U")
         same(got["V"], V_o, "V")
-        single_call_agrees(got, x.shape[1], 16 if x.dtype == np.float16 else 32)
+        single_call_agrees(got, x.shape[1], 16 if x.dtype == np.float16 else 32, got["fused"])
         if H % 2 == 0 and W % 2 == 0 and case % 2 == 0:
             # pooling fused into the store phase against pooling the unfused result of the same call
             xd, wd = torch.from_numpy(x).to(DEV), torch.from_numpy(w).to(DEV)
