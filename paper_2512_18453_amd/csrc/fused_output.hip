@@ -30,9 +30,10 @@
 // the loads issued after these are outstanding" is a count).  Every LDS address in the loop is a
 // per-lane base plus an immediate.  U comes from L2 (the whole of U is under a MB at these channel
 // counts), V from memory, once per group of 64 output channels.
-// LDS rows of 64 bytes (32 channels) are XOR-swizzled by 16-byte piece, so that the 128-bit fragment
-// reads of 16 lanes fall into 16 different bank groups; the loads fix each lane's place in LDS, so a
-// lane fetches the piece that belongs there.
+// LDS rows of 64 bytes (32 channels) are XOR-swizzled by 16-byte piece -- piece ^ ((row / 2) % 4), the
+// pattern that a 128-bit fragment read of rows lane % 16 takes fastest (timed: 2.9 clocks per wave-wide
+// read against 4.5 without it or with (row / 4) % 4, which is the right one for rows lane % 32); the
+// loads fix each lane's place in LDS, so a lane fetches the piece that belongs there.
 // At the end the m x m results of all pairs go through LDS as [32 channels][rows][columns] blocks (two
 // passes of 32 channels) and leave as in the separate output transform, with its ReLU / max-pool options.
 #include "output_common.hpp"
@@ -47,6 +48,22 @@ constexpr int kFusedWaves = 8;
 constexpr int kFusedWaveChannels = 8;  // output channels per wave
 constexpr int kFusedChannels = kFusedWaves * kFusedWaveChannels;
 constexpr int kFusedCB = 2;            // blocks of 32 input channels
+constexpr int kFusedAhead = 2;         // positions whose fragments are read ahead of the matrix instructions
+
+// The value is formed before this point of the program and used after it: arithmetic without side effects
+// is otherwise free to drift to its first use, past the matrix instructions it is meant to sit between.
+__device__ __forceinline__ void stays_here(float &x) { asm volatile("" : "+v"(x)); }
+
+template <int I, int COUNT, typename F>
+__device__ __forceinline__ void static_for_from(F &&f)
+{
+    if constexpr (I < COUNT) {
+        f(std::integral_constant<int, I>{});
+        static_for_from<I + 1, COUNT>(f);
+    }
+}
+template <int COUNT, typename F>
+__device__ __forceinline__ void static_for(F &&f) { static_for_from<0, COUNT>(f); }
 
 // fold[d][p]: d = 0: (A[0][0], 0, ..., 0); d >= 1: the coefficients of the pair of points d (A[2d - 1][p])
 template <int N, int R>
@@ -58,10 +75,11 @@ template <int N, int R, int STG>
 __global__ void __launch_bounds__(64 * kFusedWaves, 2)
 fused_contract_output_kernel(const f16 *__restrict__ U, const f16 *__restrict__ V, f16 *__restrict__ y,
                              int K, int H, int W, int tiles_h, int tiles_w, int Kp, long long Ttot, int k_groups,
-                             int relu, OutShape sh, OutCoef<N, R> coef, FoldCoef<N, R> fold)
+                             int relu, int one_pass, OutShape sh, OutCoef<N, R> coef, FoldCoef<N, R> fold)
 {
     constexpr int M = N - R + 1;
     constexpr int CB = kFusedCB;
+    constexpr int HP = (N - 2) / 2;                   // pairs of points +a, -a
     constexpr int G = N / 2;                          // positions whose U is waited for, read and refilled together
     constexpr int V_CHUNK = kFusedTiles * 64;         // bytes: 16 tiles x 32 channels
     constexpr int V_ROW = N * CB * V_CHUNK;           // one row of positions
@@ -90,18 +108,18 @@ fused_contract_output_kernel(const f16 *__restrict__ U, const f16 *__restrict__ 
     const int k0 = kg * kFusedChannels, kw0 = k0 + wave * kFusedWaveChannels;
 
     // ---- direct loads.  A 64-byte row r of a chunk holds its four 16-byte pieces in the places
-    // piece ^ ((r / 4) % 4); lane l of a load writes 16 bytes at its base + 16 l.
+    // piece ^ ((r / 2) % 4); lane l of a load writes 16 bytes at its base + 16 l.
     // V: one load = one chunk (16 tiles of one channel block): lane l -> row l / 4, place l % 4; the
     //    N * CB chunks of a row are dealt out to the waves, chunk = wave + 8 s.
     // U: one load = one position (8 channels each of the two channel blocks): lane l -> block l / 32,
     //    row (l / 4) % 8, place l % 4.
-    const int v_row_l = lane >> 2, v_piece_l = (lane & 3) ^ ((lane >> 4) & 3);
+    const int v_row_l = lane >> 2, v_piece_l = (lane & 3) ^ ((v_row_l >> 1) & 3);
     long long v_t = t0 + v_row_l;
     if (v_t > Ttot - 1) v_t = Ttot - 1;               // rows past the end: reread the last tile (never used)
     const unsigned v_lane_off = (unsigned)(((unsigned)v_t * kChanBlock + (unsigned)v_piece_l * 8u) * sizeof(f16));
     const size_t v_cb_stride = (size_t)Ttot * kChanBlock;          // elements per channel block of a position
     const size_t u_cb_stride = (size_t)Kp * kChanBlock;
-    const int u_row_l = (lane >> 2) & 7, u_piece_l = (lane & 3) ^ ((u_row_l >> 2) & 3);
+    const int u_row_l = (lane >> 2) & 7, u_piece_l = (lane & 3) ^ ((u_row_l >> 1) & 3);
     const unsigned u_lane_off = (unsigned)((((unsigned)(lane >> 5) * (unsigned)u_cb_stride) + (unsigned)(kw0 + u_row_l) * kChanBlock +
                                             (unsigned)u_piece_l * 8u) * sizeof(f16));
     const bool v_all = V_EVEN || wave + (V_LOADS - 1) * kFusedWaves < N * CB;      // this wave has a chunk in the last round
@@ -138,31 +156,30 @@ fused_contract_output_kernel(const f16 *__restrict__ U, const f16 *__restrict__ 
     // 2g + {0, 1}.  B operand (V): column lane % 16 = tile, the same channels.
     const int f_row = lane & 15, f_piece = lane >> 4;
     const int a_chan = 2 * (f_row >> 2) + (f_row & 1);                       // 0..7
-    const unsigned char *a_at = lds_raw + 2 * V_ROW + wave * U_RING + a_chan * 64 + ((f_piece ^ ((a_chan >> 2) & 3)) * 16);
-    const unsigned char *b_at = lds_raw + f_row * 64 + ((f_piece ^ ((f_row >> 2) & 3)) * 16);
+    const unsigned char *a_at = lds_raw + 2 * V_ROW + wave * U_RING + a_chan * 64 + ((f_piece ^ ((a_chan >> 1) & 3)) * 16);
+    const unsigned char *b_at = lds_raw + f_row * 64 + ((f_piece ^ ((f_row >> 1) & 3)) * 16);
 
     // ---- the lane's two pairs: tile lane % 16, channels kw0 + 2 * (lane / 16) + {0, 1}
     float Y[2][M][M];
-    float carried[2][M];              // the row before, transformed along j
 #pragma unroll
-    for (int e = 0; e < 2; ++e) {
-#pragma unroll
-        for (int q = 0; q < M; ++q) carried[e][q] = 0.0f;
+    for (int e = 0; e < 2; ++e)
 #pragma unroll
         for (int p = 0; p < M; ++p)
 #pragma unroll
             for (int q = 0; q < M; ++q) Y[e][p][q] = 0.0f;
-    }
 
-    // One row of positions: products of the row, transformed along j, into w.  BUF: the buffer of V that
-    // holds the row.  Order of this wave's loads around it: ..., V(row), U(row, first half), U(row,
-    // second half), [row starts] V(row + 1), U(row + 1, first half), U(row + 1, second half), ...
-    auto row = [&](auto buf_tag, bool more, float (&w)[2][M]) __attribute__((always_inline)) {
+    // One row of positions: the products of the row into m_out.  A half row at a time: wait for its U,
+    // then position by position -- fragment reads kFusedAhead positions ahead of the matrix instructions
+    // that take them, and between the matrix instructions a slice of the vector work on the rows before
+    // (valu0 / valu1: slice jj of the first / second half), in exactly this order (the scheduler is
+    // fenced off after every position: left alone it reads each fragment just before its use and waits).
+    // BUF: the buffer of V that holds the row.  Order of this wave's loads around it: ..., V(row),
+    // U(row, first half), U(row, second half), [row starts] V(row + 1), U(row + 1, first half), ...
+    auto row = [&](auto buf_tag, bool more, float (&m_out)[N][2], auto &&valu0, auto &&valu1) __attribute__((always_inline)) {
         constexpr int BUF = decltype(buf_tag)::value;
         // this wave's chunks of V(row) have landed: the two halves of U(row) were issued after them
         asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
         __syncthreads();              // everyone's have; everyone is done with the row before, whose buffer is free
-        float m_row[N][2];
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             // U of this half has landed.  Issued after it: first half -- the second half; second half --
@@ -172,22 +189,32 @@ fused_contract_output_kernel(const f16 *__restrict__ U, const f16 *__restrict__ 
             else if (v_all) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(G + V_LOADS) : "memory");
             else asm volatile("s_waitcnt vmcnt(%0)" : : "n"(G + V_LOADS - 1) : "memory");
             if (half == 0 && more) issue_v_row(BUF ^ 1);
+            half8 fa[G][CB], fb[G][CB];
             float4v acc[G];
-#pragma unroll
-            for (int jj = 0; jj < G; ++jj) {
+            auto read_fragments = [&](int jj) __attribute__((always_inline)) {
                 const int j = half * G + jj;
-                acc[jj] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) {
-                    const half8 a = *reinterpret_cast<const half8 *>(a_at + j * U_STAGE + cb * (U_STAGE / CB));
-                    const half8 b = *reinterpret_cast<const half8 *>(b_at + BUF * V_ROW + (j * CB + cb) * V_CHUNK);
-                    acc[jj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc[jj], 0, 0, 0);
+                    fa[jj][cb] = *reinterpret_cast<const half8 *>(a_at + j * U_STAGE + cb * (U_STAGE / CB));
+                    fb[jj][cb] = *reinterpret_cast<const half8 *>(b_at + BUF * V_ROW + (j * CB + cb) * V_CHUNK);
                 }
-            }
+            };
+#pragma unroll
+            for (int jj = 0; jj < kFusedAhead && jj < G; ++jj) read_fragments(jj);
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<G>([&](auto jj_tag) __attribute__((always_inline)) {
+                constexpr int jj = decltype(jj_tag)::value;
+                if (jj + kFusedAhead < G) read_fragments(jj + kFusedAhead);
+                acc[jj] = float4v{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) acc[jj] = __builtin_amdgcn_mfma_f32_16x16x32_f16(fa[jj][cb], fb[jj][cb], acc[jj], 0, 0, 0);
+                if (half == 0) valu0(jj_tag); else valu1(jj_tag);
+                __builtin_amdgcn_sched_barrier(0);
+            });
 #pragma unroll
             for (int jj = 0; jj < G; ++jj) {
-                m_row[half * G + jj][0] = acc[jj][0];
-                m_row[half * G + jj][1] = acc[jj][1];
+                m_out[half * G + jj][0] = acc[jj][0];
+                m_out[half * G + jj][1] = acc[jj][1];
             }
             if (more) {
                 // the places of this half are free once its fragment reads have returned
@@ -195,69 +222,114 @@ fused_contract_output_kernel(const f16 *__restrict__ U, const f16 *__restrict__ 
                 issue_u_half(half);
             }
         }
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            float v[N];
-#pragma unroll
-            for (int j = 0; j < N; ++j) v[j] = m_row[j][e];
-            output_transform_1d<N, R, true>(v, w[e], coef);
-        }
     };
 
-    issue_v_row(0);
-    issue_u_half(0);
-    issue_u_half(1);
-#pragma unroll 1
-    for (int d = 0; d < N / 2; ++d) {
-        float w[2][M];
-        row(std::integral_constant<int, 0>{}, true, w);
-        // rows 2d - 1 (+a, carried) and 2d (-a) enter through their sum and difference
-        const float *c = fold.c + d * M;
+    // Slices of the vector work.  The transform of a finished row along j, for one of the lane's two pairs:
+    // slice 0 forms the pairs' sums and differences, slice k >= 1 the outputs 2k - 2 and 2k - 1.
+    static_assert(M == 2 * (G - 1), "slices of the row transform");
+    float pair_s[HP], pair_d[HP];
+    auto transform_slice = [&](auto jj_tag, auto e_tag, const float (&m_in)[N][2], float (&out)[M]) __attribute__((always_inline)) {
+        constexpr int jj = decltype(jj_tag)::value, e = decltype(e_tag)::value;
+        if constexpr (jj == 0) {
+            float v[N];
 #pragma unroll
-        for (int e = 0; e < 2; ++e)
+            for (int j = 0; j < N; ++j) v[j] = m_in[j][e];
+            output_transform_1d_pairs<N, R>(v, pair_s, pair_d);
 #pragma unroll
-            for (int p = 0; p < M; ++p) {
+            for (int j = 0; j < HP; ++j) { stays_here(pair_s[j]); stays_here(pair_d[j]); }
+        } else {
+#pragma unroll
+            for (int i = 2 * jj - 2; i < 2 * jj; ++i) {
+                out[i] = output_transform_1d_out<N, R>(i, m_in[0][e], m_in[N - 1][e], pair_s, pair_d, coef);
+                stays_here(out[i]);
+            }
+        }
+    };
+    // The fold of the rows +a (odd, `carried`) and -a (even, `w`) of a pair of points into Y, through their
+    // sum and difference: slice k < m / 2 takes the output rows 2k and 2k + 1.
+    float carried[2][M], w[2][M];
+    auto fold_slice = [&](auto jj_tag, auto e_tag, const float *c) __attribute__((always_inline)) {
+        constexpr int jj = decltype(jj_tag)::value, e = decltype(e_tag)::value;
+        if constexpr (2 * jj < M) {
+#pragma unroll
+            for (int p = 2 * jj; p < 2 * jj + 2; ++p) {
                 const float cp = c[p];
 #pragma unroll
                 for (int q = 0; q < M; ++q) {
                     const float sd = (p & 1) ? carried[e][q] - w[e][q] : carried[e][q] + w[e][q];
                     Y[e][p][q] = fma32(cp, sd, Y[e][p][q]);
+                    stays_here(Y[e][p][q]);
                 }
             }
-        row(std::integral_constant<int, 1>{}, d + 1 < N / 2, carried);
+        }
+    };
+    constexpr std::integral_constant<int, 0> kFirst{};
+    constexpr std::integral_constant<int, 1> kSecond{};
+
+    issue_v_row(0);
+    issue_u_half(0);
+    issue_u_half(1);
+    float m_even[N][2], m_odd[N][2];
+#pragma unroll
+    for (int j = 0; j < N; ++j) m_odd[j][0] = m_odd[j][1] = 0.0f;      // "row -1"
+#pragma unroll
+    for (int q = 0; q < M; ++q) carried[1][q] = w[1][q] = 0.0f;          // "pair -1" of the second pair
+    // In turn d: row 2d while row 2d - 1 is transformed (-> carried) and the lane's second pair takes the
+    // pair of points d - 1 (for d = 0: zeros); row 2d + 1 while row 2d is transformed (-> w) and the lane's
+    // first pair takes the pair of points d (for d = 0: "row -1", zeros, and row 0, the point 0).
+#pragma unroll 1
+    for (int d = 0; d < N / 2; ++d) {
+        const float *c_before = fold.c + (d > 0 ? d - 1 : 0) * M;
+        const float *c_this = fold.c + d * M;
+        row(kFirst, true, m_even,
+            [&](auto jj) __attribute__((always_inline)) { transform_slice(jj, kFirst, m_odd, carried[0]); fold_slice(jj, kSecond, c_before); },
+            [&](auto jj) __attribute__((always_inline)) { transform_slice(jj, kSecond, m_odd, carried[1]); });
+        row(kSecond, d + 1 < N / 2, m_odd,
+            [&](auto jj) __attribute__((always_inline)) { transform_slice(jj, kFirst, m_even, w[0]); },
+            [&](auto jj) __attribute__((always_inline)) { transform_slice(jj, kSecond, m_even, w[1]); fold_slice(jj, kFirst, c_this); });
     }
+    static_for<G>([&](auto jj) __attribute__((always_inline)) { fold_slice(jj, kSecond, fold.c + (N / 2 - 1) * M); });
     // row n - 1: the point at infinity
 #pragma unroll
-    for (int e = 0; e < 2; ++e)
+    for (int e = 0; e < 2; ++e) {
+        float v[N], last[M];
 #pragma unroll
-        for (int q = 0; q < M; ++q) Y[e][M - 1][q] = fma32(coef.inf, carried[e][q], Y[e][M - 1][q]);
+        for (int j = 0; j < N; ++j) v[j] = m_odd[j][e];
+        output_transform_1d<N, R, true>(v, last, coef);
+#pragma unroll
+        for (int q = 0; q < M; ++q) Y[e][M - 1][q] = fma32(coef.inf, last[q], Y[e][M - 1][q]);
+    }
 
-    // ---- the results leave through LDS, 32 channels at a time
+    // ---- the results leave through LDS: all 64 channels at once if the block fits, else 32 at a time
     f16 *stage = reinterpret_cast<f16 *>(lds_raw);
     const int tile = lane & 15;
     int jr = 0, jc = tile;
     if (sh.trb > 1) { jr = tile / tiles_w; jc = tile - jr * tiles_w; }
     const bool active = tile < sh.twb && tc0 + jc < tiles_w && tr + jr < tiles_h;
+    const float floor_at = relu ? 0.0f : -__builtin_inff();          // val < floor ? floor : val keeps a NaN
+    constexpr int KB = kFusedChannels / kChanBlock;
+    const int per_pass = one_pass ? KB : 1;
 #pragma unroll 1
-    for (int pass = 0; pass < kFusedChannels / kChanBlock; ++pass) {
+    for (int pass = 0; pass < KB; pass += per_pass) {
         __syncthreads();              // the operand buffers (first pass) or the block before have been read
-        if (active && (wave >> 2) == pass) {
+        if (active && (one_pass || (wave >> 2) == pass)) {
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const int k_in = (wave & 3) * kFusedWaveChannels + 2 * (lane >> 4) + e;
+                const int k_in = (one_pass ? wave : (wave & 3)) * kFusedWaveChannels + 2 * (lane >> 4) + e;
                 f16 *dst = stage + k_in * sh.k_pitch + jr * M * sh.cols_pitch + jc * M;
 #pragma unroll
                 for (int p = 0; p < M; ++p)
 #pragma unroll
                     for (int q = 0; q < M; ++q) {
-                        float val = Y[e][p][q];
-                        if (relu) val = val < 0.0f ? 0.0f : val;      // NaN stays NaN
-                        dst[p * sh.cols_pitch + q] = (f16)val;
+                        const float val = Y[e][p][q];
+                        dst[p * sh.cols_pitch + q] = (f16)(val < floor_at ? floor_at : val);
                     }
             }
         }
         __syncthreads();
-        store_output_block<f16, M, STG>(stage, y, img, k0 / kChanBlock + pass, tr, tc0, K, H, W, tiles_w, sh);
+        for (int blk = 0; blk < per_pass; ++blk)
+            store_output_block<f16, M, STG>(stage + blk * kChanBlock * sh.k_pitch, y, img, k0 / kChanBlock + pass + blk, tr, tc0,
+                                            K, H, W, tiles_w, sh);
     }
 }
 
@@ -285,7 +357,9 @@ static int launch_fused_shape(const nova_transforms *t, const void *U, const voi
     }
     const size_t stage_bytes = out_shape<N, R, f16>(twb, trb, sh);
     const size_t loop_bytes = (size_t)2 * N * CB * kFusedTiles * 64 + (size_t)kFusedWaves * N * CB * kFusedWaveChannels * 64;
-    const size_t lds_bytes = stage_bytes > loop_bytes ? stage_bytes : loop_bytes;
+    const int one_pass = 2 * stage_bytes <= 160 * 1024 ? 1 : 0;       // both blocks of 32 channels staged together
+    const size_t out_bytes = one_pass ? 2 * stage_bytes : stage_bytes;
+    const size_t lds_bytes = out_bytes > loop_bytes ? out_bytes : loop_bytes;
     if (lds_bytes > 160 * 1024 || sh.twb > kFusedTiles) return (int)hipErrorInvalidValue;
     // 32-bit byte offsets inside one position of V
     if ((size_t)CB * g.T * kChanBlock * sizeof(f16) >= ((size_t)1 << 32)) return (int)hipErrorInvalidValue;
@@ -313,7 +387,7 @@ static int launch_fused_shape(const nova_transforms *t, const void *U, const voi
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * kFusedWaves), lds_bytes, stream,
                        (const f16 *)U, (const f16 *)V, (f16 *)y, g.K, g.H, g.W, g.tiles_h, g.tiles_w, g.Kp, g.T, k_groups,
-                       (flags & NOVA_FLAG_RELU) ? 1 : 0, sh, coef, fold);
+                       (flags & NOVA_FLAG_RELU) ? 1 : 0, one_pass, sh, coef, fold);
     return (int)hipGetLastError();
 }
 

@@ -7,6 +7,36 @@
 
 namespace nova {
 
+// The 1D transform with A for points in the paired order (0, +a1, -a1, ..., infinity), in two steps that
+// can be issued apart: sums and differences of the pairs, then one output at a time.
+template <int N, int R>
+__device__ __forceinline__ void output_transform_1d_pairs(const float (&v)[N], float (&s)[(N - 2) / 2 > 0 ? (N - 2) / 2 : 1],
+                                                          float (&d)[(N - 2) / 2 > 0 ? (N - 2) / 2 : 1])
+{
+    constexpr int H = (N - 2) / 2;
+#pragma unroll
+    for (int j = 0; j < H; ++j) {
+        s[j] = v[2 * j + 1] + v[2 * j + 2];
+        d[j] = v[2 * j + 1] - v[2 * j + 2];
+    }
+}
+
+// output i from the values at 0 and at infinity and the pairs' sums and differences
+// (with unscaled rows zero = inf = pw[j][0] = 1 and these are plain sums)
+template <int N, int R>
+__device__ __forceinline__ float output_transform_1d_out(int i, float v_zero, float v_inf,
+                                                         const float (&s)[(N - 2) / 2 > 0 ? (N - 2) / 2 : 1],
+                                                         const float (&d)[(N - 2) / 2 > 0 ? (N - 2) / 2 : 1], const OutCoef<N, R> &k)
+{
+    constexpr int M = N - R + 1;
+    constexpr int H = (N - 2) / 2;
+    float acc = i == 0 ? k.zero * v_zero : (i == M - 1) ? k.inf * v_inf : 0.0f;
+#pragma unroll
+    for (int j = 0; j < H; ++j) acc = fma32(k.pw[j * M + i], (i & 1) ? d[j] : s[j], acc);
+    if (M == 1) acc = fma32(k.inf, v_inf, acc);
+    return acc;
+}
+
 template <int N, int R, bool SYM>
 __device__ __forceinline__ void output_transform_1d(const float (&v)[N], float (&out)[N - R + 1], const OutCoef<N, R> &k)
 {
@@ -14,24 +44,9 @@ __device__ __forceinline__ void output_transform_1d(const float (&v)[N], float (
     constexpr int H = (N - 2) / 2;
     if constexpr (SYM) {
         float s[H > 0 ? H : 1], d[H > 0 ? H : 1];
+        output_transform_1d_pairs<N, R>(v, s, d);
 #pragma unroll
-        for (int j = 0; j < H; ++j) {
-            s[j] = v[2 * j + 1] + v[2 * j + 2];
-            d[j] = v[2 * j + 1] - v[2 * j + 2];
-        }
-        // (with unscaled rows zero = inf = pw[j][0] = 1 and these are plain sums)
-        float y0 = k.zero * v[0];
-#pragma unroll
-        for (int j = 0; j < H; ++j) y0 = fma32(k.pw[j * M], s[j], y0);
-        out[0] = y0;
-#pragma unroll
-        for (int i = 1; i < M; ++i) {
-            float acc = (i == M - 1) ? k.inf * v[N - 1] : 0.0f;
-#pragma unroll
-            for (int j = 0; j < H; ++j) acc = fma32(k.pw[j * M + i], (i & 1) ? d[j] : s[j], acc);
-            out[i] = acc;
-        }
-        if constexpr (M == 1) out[0] = fma32(k.inf, v[N - 1], out[0]);
+        for (int i = 0; i < M; ++i) out[i] = output_transform_1d_out<N, R>(i, v[0], v[N - 1], s, d, k);
     } else {
 #pragma unroll
         for (int i = 0; i < M; ++i) {
