@@ -173,8 +173,8 @@ int nova::conv2d_with_workspace(const nova_transforms *t, const void *x, const v
     if ((flags & NOVA_FLAG_POOL2) && (H % 2 != 0 || W % 2 != 0)) return NOVA_EINVAL;
     const int m = t->m, r = t->r;
 
-    // (few input channels at large K: contraction and output transform run as one kernel and keep no M)
-    const bool fused = fused_contract_output_applies(t, make_geometry(1, C, H, W, K, m, r), dtype, flags);
+    // (64 input channels: contraction and output transform run as one kernel and keep no M, where that is faster)
+    const bool fused = fused_contract_output_preferred(t, make_geometry(1, C, H, W, K, m, r), dtype, flags);
     // largest slab (whole images) whose V and M fit the workspace; slab_bytes grows with the count
     auto slab_bytes = [&](long long count, size_t *v_part) {
         const Geometry sg = make_geometry((int)count, C, H, W, K, m, r);

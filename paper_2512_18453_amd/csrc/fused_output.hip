@@ -48,7 +48,6 @@ constexpr int kFusedWaves = 8;
 constexpr int kFusedWaveChannels = 8;  // output channels per wave
 constexpr int kFusedChannels = kFusedWaves * kFusedWaveChannels;
 constexpr int kFusedCB = 2;            // blocks of 32 input channels
-constexpr int kFusedAhead = 2;         // positions whose fragments are read ahead of the matrix instructions
 
 // The value is formed before this point of the program and used after it: arithmetic without side effects
 // is otherwise free to drift to its first use, past the matrix instructions it is meant to sit between.
@@ -81,6 +80,7 @@ fused_contract_output_kernel(const f16 *__restrict__ U, const f16 *__restrict__ 
     constexpr int CB = kFusedCB;
     constexpr int HP = (N - 2) / 2;                   // pairs of points +a, -a
     constexpr int G = N / 2;                          // positions whose U is waited for, read and refilled together
+    constexpr int kFusedAhead = 2;                    // positions whose fragments are read ahead of the matrix instructions
     constexpr int V_CHUNK = kFusedTiles * 64;         // bytes: 16 tiles x 32 channels
     constexpr int V_ROW = N * CB * V_CHUNK;           // one row of positions
     constexpr int U_STAGE = CB * kFusedWaveChannels * 64;     // bytes of one position: 2 blocks x 8 channels x 32 channels in
@@ -397,6 +397,14 @@ bool fused_contract_output_applies(const nova_transforms *t, const Geometry &g, 
 {
     return dtype == NOVA_F16 && !(flags & NOVA_FLAG_M_F16) && t->symmetric && t->r == 3 && (t->n == 8 || t->n == 10) &&
            g.C == kFusedCB * kChanBlock && g.K % kFusedChannels == 0 && g.T <= 0x7fffffffLL;
+}
+
+// ... and those for which it is the faster way (measured against contraction + output transform on one
+// MI355X): every F(8,3) shape it takes; F(6,3) -- more tiles per image, fewer outputs per tile -- only where one
+// group of 16 tiles spans a tile row (images up to 96 wide), elsewhere the two are level.
+bool fused_contract_output_preferred(const nova_transforms *t, const Geometry &g, int dtype, int flags)
+{
+    return fused_contract_output_applies(t, g, dtype, flags) && (t->n == 10 || g.tiles_w <= kFusedTiles);
 }
 
 int launch_fused_contract_output(const nova_transforms *t, const void *U, const void *V, void *y, const Geometry &g,

@@ -108,8 +108,10 @@ int launch_contract(const nova_transforms *t, const void *U, const void *V, void
                     const Geometry &g, int dtype, int flags, void *stream);
 int launch_output_transform(const nova_transforms *t, const void *M, void *y, const Geometry &g,
                             int dtype, int flags, void *stream);
-// Contraction and output transform in one kernel (no M), for the shapes fused_contract_output_applies names
+// Contraction and output transform in one kernel (no M), for the shapes fused_contract_output_applies names;
+// nova_winograd_conv2d takes it for those fused_contract_output_preferred names
 bool fused_contract_output_applies(const nova_transforms *t, const Geometry &g, int dtype, int flags);
+bool fused_contract_output_preferred(const nova_transforms *t, const Geometry &g, int dtype, int flags);
 int launch_fused_contract_output(const nova_transforms *t, const void *U, const void *V, void *y, const Geometry &g,
                                  int dtype, int flags, void *stream);
 // Few input channels (C <= few_channels_limit()): the output transform forms the products itself

@@ -109,10 +109,15 @@ def same(got, want, what):
     raise AssertionError("\n".join(lines))
 
 
-def takes_fused_path(t, C, K, dtype, flags=0):
-    """Shapes for which nova_winograd_conv2d runs contraction and output transform as one kernel."""
-    return (dtype == np.float16 and not flags & nova.NOVA_FLAG_M_F16 and t.symmetric and t.r == 3 and t.n in (8, 10)
-            and C == 64 and K % 64 == 0)
+def takes_fused_path(t, C, K, dtype, flags=0, W=None):
+    """Shapes for which nova_winograd_conv2d runs contraction and output transform as one kernel: F(8,3) always,
+    F(6,3) where 16 tiles span the image width (W: the width, if it matters to the caller)."""
+    ok = (dtype == np.float16 and not flags & nova.NOVA_FLAG_M_F16 and t.symmetric and t.r == 3 and t.n in (8, 10)
+          and C == 64 and K % 64 == 0)
+    if ok and t.n == 8:
+        assert W is not None
+        ok = -(-W // t.m) <= 16
+    return ok
 
 
 def single_call_agrees(got, C, storage, fused=False):
@@ -158,7 +163,7 @@ def run_stages(t, x, w, flags=0):
     y = nova.nova_output_transform(t, M, N, K, H, W, xd.dtype, flags)
     y2 = nova.nova_winograd_conv2d(t, xd, U, K, flags=flags, images_per_slab=1)
     torch.cuda.synchronize()
-    fused = takes_fused_path(t, C, K, x.dtype, flags)
+    fused = takes_fused_path(t, C, K, x.dtype, flags, W=W)
     Kp = -(-K // 32) * 32
     Ul = unblock(U, n2, Kp, C)
     assert not Ul[:, K:, :].any()                       # padding rows are zero
@@ -781,7 +786,7 @@ FUSED_CASES = [
 @pytest.mark.parametrize("m,N,C,K,H,W", FUSED_CASES)
 def test_fused_contraction_and_output_transform(m, N, C, K, H, W):
     # steps 3 and 4 in one kernel (no M): against the emulation, element by element, with ReLU and the
-    # fused max-pool; and nova_winograd_conv2d takes this path for these shapes
+    # fused max-pool; and nova_winograd_conv2d takes this path where it is the faster one
     say(f"[case] fused contraction + output transform F({m},3) N={N} C={C} K={K} H={H} W={W}")
     points = synth.point_set("nova", m)
     t = nova.nova_make_transforms(points, m, 3)
@@ -793,7 +798,10 @@ def test_fused_contraction_and_output_transform(m, N, C, K, H, W):
     y_relu = nova.nova_contract_output_fused(t, U, V, N, C, H, W, K, flags=nova.NOVA_FLAG_RELU)
     y_call = nova.nova_winograd_conv2d(t, xd, U, K, images_per_slab=1)
     torch.cuda.synchronize()
-    assert torch.equal(y, y_call)
+    if takes_fused_path(t, C, K, x.dtype, W=W):
+        assert torch.equal(y, y_call)
+    else:        # the single call keeps the separate kernels for this shape: another summation order
+        assert rel_l2(y.cpu().numpy().astype(np.float64), y_call.cpu().numpy().astype(np.float64)) < 2e-3
     assert torch.equal(y_relu, torch.clamp(y, min=0))
     sample = [0, N - 1] if H * W > 10000 else list(range(N))
     x64, w64 = x[sample].astype(np.float64), w.astype(np.float64)
