@@ -87,9 +87,17 @@ def main():
     t = nova.nova_make_transforms(points, m, 3)
     U = nova.nova_filter_transform(t, wd)
     ws_bytes = nova.nova_conv2d_workspace_bytes(N, C, H, W, K, m, dt, flags, args.images_per_slab)
-    slab_imgs = next(s for s in range(N, 0, -1)
-                     if nova.nova_conv2d_workspace_bytes(N, C, H, W, K, m, dt, flags, s) <= ws_bytes)
-    n_slabs = -(-N // slab_imgs)
+    # the slabs nova_winograd_conv2d cuts the batch into with this workspace: as many images as fit (V and M of a
+    # slab, or V alone where contraction and output transform run as one kernel), then slabs of equal size
+    path = nova.nova_conv2d_path(t, C, H, W, K, dt, flags)
+    fused = path == nova.NOVA_PATH_FUSED_OUTPUT      # contraction and output transform are one kernel, no M
+    if fused:
+        fits = next(s for s in range(N, 0, -1) if nova.nova_input_bytes(s, C, H, W, m, dt) <= ws_bytes)
+    else:
+        fits = next(s for s in range(N, 0, -1)
+                    if nova.nova_conv2d_workspace_bytes(N, C, H, W, K, m, dt, flags, s) <= ws_bytes)
+    n_slabs = -(-N // fits)
+    slab_imgs = -(-N // n_slabs)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     y = torch.empty((N, K, H, W), dtype=tdtype, device=dev)
 
@@ -130,9 +138,13 @@ def main():
             ev[0].record()
             nova.nova_input_transform(t, xd[i0:i0 + cnt], V=V)
             ev[1].record()
-            nova.nova_contract(t, U, V, cnt, C, H, W, K, flags, M=M)
-            ev[2].record()
-            nova.nova_output_transform(t, M, cnt, K, H, W, tdtype, flags, y=y[i0:i0 + cnt])
+            if fused:
+                nova.nova_contract_output_fused(t, U, V, cnt, C, H, W, K, flags, y=y[i0:i0 + cnt])
+                ev[2].record()
+            else:
+                nova.nova_contract(t, U, V, cnt, C, H, W, K, flags, M=M)
+                ev[2].record()
+                nova.nova_output_transform(t, M, cnt, K, H, W, tdtype, flags, y=y[i0:i0 + cnt])
             ev[3].record()
             if rep >= 3 and cnt == slab_imgs:
                 marks.append(ev)
@@ -144,12 +156,15 @@ def main():
     M_b = n * n * T_slab * kb * m_es
     U_b = n * n * kb * cb * es
     gemm_flop = 2.0 * n * n * T_slab * C * K
-    stages = {
-        "input_transform": dict(us=s_in * 1e6, bytes=x_b + V_b, gbs=(x_b + V_b) / s_in / 1e9),
-        "contract": dict(us=s_c * 1e6, bytes=U_b + V_b + M_b, gbs=(U_b + V_b + M_b) / s_c / 1e9,
-                         tflops=gemm_flop / s_c / 1e12, mfma_frac=gemm_flop / s_c / 1e12 / MFMA_F16_PEAK_TFLOPS),
-        "output_transform": dict(us=s_out * 1e6, bytes=M_b + y_b, gbs=(M_b + y_b) / s_out / 1e9),
-    }
+    stages = {"input_transform": dict(us=s_in * 1e6, bytes=x_b + V_b, gbs=(x_b + V_b) / s_in / 1e9)}
+    if fused:
+        stages["contract_output_fused"] = dict(us=s_c * 1e6, bytes=U_b + V_b + y_b, gbs=(U_b + V_b + y_b) / s_c / 1e9,
+                                               tflops=gemm_flop / s_c / 1e12,
+                                               mfma_frac=gemm_flop / s_c / 1e12 / MFMA_F16_PEAK_TFLOPS)
+    else:
+        stages["contract"] = dict(us=s_c * 1e6, bytes=U_b + V_b + M_b, gbs=(U_b + V_b + M_b) / s_c / 1e9,
+                                  tflops=gemm_flop / s_c / 1e12, mfma_frac=gemm_flop / s_c / 1e12 / MFMA_F16_PEAK_TFLOPS)
+        stages["output_transform"] = dict(us=s_out * 1e6, bytes=M_b + y_b, gbs=(M_b + y_b) / s_out / 1e9)
     for st in stages.values():
         st["hbm_frac"] = st["gbs"] / HBM_PEAK_GBS
     dominant = max(stages, key=lambda k: stages[k]["us"])
@@ -161,7 +176,7 @@ def main():
                     launch_us=round(dom["us"], 2), algorithmic_bytes=dom["bytes"])
     # the contraction against both of its bounds: the matrix cores' peak, and what its operand and
     # result bytes allow at the HBM peak (the binding one at these shapes)
-    c_st = stages["contract"]
+    c_st = stages["contract_output_fused" if fused else "contract"]
     c_floor_us = max(gemm_flop / (MFMA_F16_PEAK_TFLOPS * 1e12), c_st["bytes"] / (HBM_PEAK_GBS * 1e9)) * 1e6
     c_st["attainable_us"] = c_floor_us
     c_st["frac_of_attainable"] = c_floor_us / c_st["us"]
@@ -283,7 +298,8 @@ def main():
         "dtype": "f16" if dt == nova.NOVA_F16 else "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: 3x3 conv N={N} C={C} K={K} H=W={H}, F({m},3), {args.points} points",
                    "points": args.points, "images_per_slab": int(slab_imgs), "slabs": int(n_slabs),
-                   "products_dtype": "f16" if m_es == 2 else "f32"},
+                   "products_dtype": "f16" if m_es == 2 else "f32",
+                   "kernels": ["stages", "few_channels", "fused_output"][path]},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "stages": {k: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()}

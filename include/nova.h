@@ -328,13 +328,20 @@ int nova_winograd_conv2d_int8(const nova_transforms *t, const void *x, const voi
 
 /*
  * Steps 3 and 4 (Sec. 2.1) in one kernel: y = A^T [ sum_c U * V ] A per tile and output channel, the
- * products kept in registers and never written as M.  For layers with few input channels, where M is
+ * products kept in registers and never written as M.  For layers with 64 input channels, where M is
  * most of the memory traffic: NOVA_F16 storage, points in the order 0, +a, -a, .., F(6,3) or F(8,3),
- * C = 64 or 128, K a multiple of 64, without NOVA_FLAG_M_F16; other requests: NOVA_EUNSUPPORTED.
- * nova_winograd_conv2d takes this path by itself for such shapes (its result then differs from
- * nova_contract + nova_output_transform by the summation order of the matrix unit only).
- * U, V as for nova_contract; y, flags (ReLU, max-pool) as for nova_output_transform.
+ * C = 64, K a multiple of 64, without NOVA_FLAG_M_F16; other requests: NOVA_EUNSUPPORTED.
+ * U, V as for nova_contract; y, flags (ReLU, max-pool) as for nova_output_transform.  The result differs
+ * from nova_contract + nova_output_transform by the order of the binary32 sums only.
+ *
+ * nova_conv2d_path says which kernels nova_winograd_conv2d runs for a layer shape (whatever the batch):
+ * NOVA_PATH_STAGES (input transform, contraction, output transform), NOVA_PATH_FEW_CHANNELS (at most 4
+ * input channels: compact V, the products formed inside the output transform) or NOVA_PATH_FUSED_OUTPUT
+ * (input transform, then the kernel above: taken where it is supported and measured faster -- every
+ * F(8,3) shape, F(6,3) where 16 tiles span the image width).  Negative: an error code.  Host only.
  */
+enum { NOVA_PATH_STAGES = 0, NOVA_PATH_FEW_CHANNELS = 1, NOVA_PATH_FUSED_OUTPUT = 2 };
+int nova_conv2d_path(const nova_transforms *t, int C, int H, int W, int K, int dtype, int flags);
 int nova_contract_output_fused(const nova_transforms *t, const void *U, const void *V, void *y,
                                int N, int C, int H, int W, int K, int dtype, int flags, void *stream);
 

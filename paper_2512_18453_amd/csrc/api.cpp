@@ -162,6 +162,15 @@ extern "C" int nova_contract_output_fused(const nova_transforms *t, const void *
     return hip_result(launch_fused_contract_output(t, U, V, y, g, dtype, flags, stream));
 }
 
+extern "C" int nova_conv2d_path(const nova_transforms *t, int C, int H, int W, int K, int dtype, int flags)
+{
+    if (int rc = check_handle(t)) return rc;
+    if (!dims_ok(1, C, H, W, K) || !dtype_ok(dtype)) return NOVA_EINVAL;
+    if (few_channels(C)) return NOVA_PATH_FEW_CHANNELS;
+    return fused_contract_output_preferred(t, make_geometry(1, C, H, W, K, t->m, t->r), dtype, flags) ? NOVA_PATH_FUSED_OUTPUT
+                                                                                                      : NOVA_PATH_STAGES;
+}
+
 // The slab loop behind nova_winograd_conv2d and nova_winograd_conv2d_static.
 int nova::conv2d_with_workspace(const nova_transforms *t, const void *x, const void *U, void *y, int N,
                                 int C, int H, int W, int K, int dtype, int flags, void *workspace,
@@ -351,4 +360,4 @@ extern "C" const char *nova_strerror(int code)
 }
 
 extern "C" int nova_last_hip_error(void) { return g_last_hip_error; }
-extern "C" const char *nova_version(void) { return "libnova 0.2 (gfx950)"; }
+extern "C" const char *nova_version(void) { return "libnova 0.3 (gfx950)"; }

@@ -17,6 +17,7 @@ NOVA_ROWS_PLAIN, NOVA_ROWS_BALANCED, NOVA_ROWS_GIVEN = 0, 1, 2
 NOVA_MATRIX_F32, NOVA_MATRIX_F16, NOVA_MATRIX_INT8 = 0, 1, 2
 NOVA_FLAG_RELU, NOVA_FLAG_M_F16, NOVA_FLAG_POOL2 = 1, 2, 4
 NOVA_INT8_PER_TENSOR, NOVA_INT8_PER_CHANNEL, NOVA_INT8_PER_POSITION = 0, 1, 2
+NOVA_PATH_STAGES, NOVA_PATH_FEW_CHANNELS, NOVA_PATH_FUSED_OUTPUT = 0, 1, 2
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnova.so")
 _lib = None
@@ -26,7 +27,7 @@ EXPORTS = [
     "nova_get_matrix_f64", "nova_get_matrix_f32", "nova_kappa", "nova_filter_bytes", "nova_input_bytes",
     "nova_product_bytes", "nova_filter_transform", "nova_conv2d_workspace_bytes", "nova_winograd_conv2d",
     "nova_winograd_conv2d_static", "nova_static_workspace_bytes",
-    "nova_contract_output_fused", "nova_es_fitness", "nova_es_normals_needed", "nova_evolution_strategy", "nova_snap_points",
+    "nova_contract_output_fused", "nova_conv2d_path", "nova_es_fitness", "nova_es_normals_needed", "nova_evolution_strategy", "nova_snap_points",
     "nova_filter_int8_bytes", "nova_input_int8_bytes", "nova_quantize_filter_int8", "nova_quantize_input_int8",
     "nova_contract_int8", "nova_conv2d_int8_workspace_bytes", "nova_winograd_conv2d_int8",
     "nova_input_transform", "nova_contract", "nova_output_transform", "nova_relu_maxpool2x2",
@@ -99,6 +100,7 @@ def lib():
         L.nova_conv2d_int8_workspace_bytes.restype = sz
         L.nova_winograd_conv2d_int8.argtypes = [vp, vp, vp, vp, i, vp, i, i, i, i, i, i, i, vp, sz, vp]
         L.nova_contract_output_fused.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
+        L.nova_conv2d_path.argtypes = [vp, i, i, i, i, i, i]
         L.nova_input_transform.argtypes = [vp, vp, vp, sz, i, i, i, i, i, vp]
         L.nova_contract.argtypes = [vp, vp, vp, vp, sz, i, i, i, i, i, i, i, vp]
         L.nova_output_transform.argtypes = [vp, vp, sz, vp, i, i, i, i, i, i, vp]
@@ -420,6 +422,13 @@ def nova_contract_output_fused(t, U, V, N, C, H, W, K, flags=0, y=None):
     _check(lib().nova_contract_output_fused(t.handle, _dev(U), _dev(V), _dev(y), N, C, H, W, K, _dtype_code(V), flags,
                                             _stream()), "nova_contract_output_fused")
     return y
+
+
+def nova_conv2d_path(t, C, H, W, K, dtype_code, flags=0):
+    """Which kernels nova_winograd_conv2d runs for this layer shape (NOVA_PATH_*).  dtype_code: NOVA_F16 / NOVA_F32."""
+    rc = lib().nova_conv2d_path(t.handle, C, H, W, K, dtype_code, flags)
+    _check(min(rc, 0), "nova_conv2d_path")
+    return rc
 
 
 def nova_relu_maxpool2x2(x, out=None):

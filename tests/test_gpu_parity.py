@@ -109,15 +109,10 @@ def same(got, want, what):
     raise AssertionError("\n".join(lines))
 
 
-def takes_fused_path(t, C, K, dtype, flags=0, W=None):
-    """Shapes for which nova_winograd_conv2d runs contraction and output transform as one kernel: F(8,3) always,
-    F(6,3) where 16 tiles span the image width (W: the width, if it matters to the caller)."""
-    ok = (dtype == np.float16 and not flags & nova.NOVA_FLAG_M_F16 and t.symmetric and t.r == 3 and t.n in (8, 10)
-          and C == 64 and K % 64 == 0)
-    if ok and t.n == 8:
-        assert W is not None
-        ok = -(-W // t.m) <= 16
-    return ok
+def takes_fused_path(t, C, K, dtype, flags=0, H=56, W=56):
+    """Whether nova_winograd_conv2d runs contraction and output transform as one kernel for this shape."""
+    code = nova.NOVA_F16 if dtype == np.float16 else nova.NOVA_F32
+    return nova.nova_conv2d_path(t, C, H, W, K, code, flags) == nova.NOVA_PATH_FUSED_OUTPUT
 
 
 def single_call_agrees(got, C, storage, fused=False):
@@ -163,7 +158,7 @@ def run_stages(t, x, w, flags=0):
     y = nova.nova_output_transform(t, M, N, K, H, W, xd.dtype, flags)
     y2 = nova.nova_winograd_conv2d(t, xd, U, K, flags=flags, images_per_slab=1)
     torch.cuda.synchronize()
-    fused = takes_fused_path(t, C, K, x.dtype, flags, W=W)
+    fused = takes_fused_path(t, C, K, x.dtype, flags, H=H, W=W)
     Kp = -(-K // 32) * 32
     Ul = unblock(U, n2, Kp, C)
     assert not Ul[:, K:, :].any()                       # padding rows are zero
@@ -798,7 +793,7 @@ def test_fused_contraction_and_output_transform(m, N, C, K, H, W):
     y_relu = nova.nova_contract_output_fused(t, U, V, N, C, H, W, K, flags=nova.NOVA_FLAG_RELU)
     y_call = nova.nova_winograd_conv2d(t, xd, U, K, images_per_slab=1)
     torch.cuda.synchronize()
-    if takes_fused_path(t, C, K, x.dtype, W=W):
+    if takes_fused_path(t, C, K, x.dtype, H=H, W=W):
         assert torch.equal(y, y_call)
     else:        # the single call keeps the separate kernels for this shape: another summation order
         assert rel_l2(y.cpu().numpy().astype(np.float64), y_call.cpu().numpy().astype(np.float64)) < 2e-3

@@ -271,3 +271,21 @@ def test_snap_points_equals_oracle():
         assert got == want and kappa_l == pytest.approx(kappa_o, rel=1e-10)
     want, _ = discovery.snap_points([0.1, 0.1001, -0.7], 2, 3, d_max=4)
     assert nova.nova_snap_points(2, 3, [0.1, 0.1001, -0.7], d_max=4)[0] == want
+
+
+def test_conv2d_path_names_the_kernels_of_a_layer_shape():
+    # host-side decision only: which kernels nova_winograd_conv2d would launch
+    t8 = nova.nova_make_transforms(synth.point_set("nova", 8), 8, 3)
+    t6 = nova.nova_make_transforms(synth.point_set("nova", 6), 6, 3)
+    t4 = nova.nova_make_transforms(synth.point_set("nova", 4), 4, 3)
+    F16, F32 = nova.NOVA_F16, nova.NOVA_F32
+    assert nova.nova_conv2d_path(t8, 3, 224, 224, 64, F16) == nova.NOVA_PATH_FEW_CHANNELS
+    assert nova.nova_conv2d_path(t8, 64, 224, 224, 64, F16) == nova.NOVA_PATH_FUSED_OUTPUT
+    assert nova.nova_conv2d_path(t8, 64, 17, 23, 192, F16) == nova.NOVA_PATH_FUSED_OUTPUT
+    assert nova.nova_conv2d_path(t6, 64, 56, 56, 64, F16) == nova.NOVA_PATH_FUSED_OUTPUT      # 10 tiles across
+    assert nova.nova_conv2d_path(t6, 64, 112, 112, 64, F16) == nova.NOVA_PATH_STAGES          # 19 tiles across
+    for (t, C, K, dt, flags) in ((t8, 128, 128, F16, 0), (t8, 64, 96, F16, 0), (t8, 64, 64, F32, 0),
+                                 (t8, 64, 64, F16, nova.NOVA_FLAG_M_F16), (t4, 64, 64, F16, 0), (t8, 256, 256, F16, 0)):
+        assert nova.nova_conv2d_path(t, C, 56, 56, K, dt, flags) == nova.NOVA_PATH_STAGES
+    with pytest.raises(nova.NovaError):
+        nova.nova_conv2d_path(t8, 0, 56, 56, 64, F16)
