@@ -101,8 +101,8 @@ int nova_make_transforms(const nova_rational *finite_points, int n_points, int m
  *
  * matrix_dtype -- what the device constants are rounded to (each entry once, from the exact value):
  *   NOVA_MATRIX_F32  A, B^T binary32, G binary64 (the default of nova_make_transforms)
- *   NOVA_MATRIX_F16  every entry to the nearest binary16 first ("matrices stored in float16",
- *                    Table "FP16 storage"); the rounded tables then hold those values
+ *   NOVA_MATRIX_F16  every entry to the nearest binary16 first (the variant with the matrices kept in
+ *                    binary16: Sec. "Float16 Precision Analysis", Table "FP16 storage"); the rounded tables then hold those values
  *   NOVA_MATRIX_INT8 each of A, B^T, G quantised symmetrically per tensor (Sec. "INT8 Convolution
  *                    Error Validation"): scale s = max|entry| / 127, code = entry / s rounded to
  *                    nearest (ties to even) and saturated to [-128, 127], both computed exactly;

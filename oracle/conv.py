@@ -144,7 +144,7 @@ def winograd_conv2d_emulated(x, g, points, m, storage=16, m_storage=32, v_exact=
     """Winograd with the intermediate tensors rounded as the fp16 (storage=16) or fp32
     (storage=32) device path rounds them.  x and g must already be exact in the storage
     format.  transform_dtype 'f32' keeps A and B^T as binary32 constants, 'f16' first rounds
-    every matrix entry to binary16 ("matrices stored in float16"), 'int8' first quantises each
+    every matrix entry to binary16 (the variant of Sec. "Float16 Precision Analysis"), 'int8' first quantises each
     matrix to INT8 per tensor (cook_toom.quantize_int8; the de-quantised values are then held as
     binary32 / binary64 constants).
     row_scaling: None, "balanced", or (log2_b, log2_g) -- power-of-two row scales applied to

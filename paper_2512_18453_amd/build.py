@@ -2,6 +2,7 @@
 
     python -m paper_2512_18453_amd.build            # compile what changed, link
     python -m paper_2512_18453_amd.build --force    # compile everything
+    python -m paper_2512_18453_amd.build --sanitize # host sources under AddressSanitizer + UBSan (no GPU code)
 
 hipcc cross-compiles for gfx950 without a GPU.  -ffp-contract=off: the kernels spell out
 every fused multiply-add themselves, because the binary32 input transform has a fixed
@@ -54,5 +55,35 @@ def build(force=False):
     return LIB
 
 
+SANITIZE = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-static-libasan",
+            "-static-libubsan", "-fno-omit-frame-pointer"]
+
+
+def sanitize_selftest():
+    """The host-only sources of the library (exact construction, point discovery) and the oracle's C loops,
+    each compiled with AddressSanitizer and UndefinedBehaviorSanitizer into a program of its own that walks
+    through their entry points (csrc/host_selftest.cpp, oracle/conv_oracle_selftest.c), and run.  Programs
+    rather than a sanitized libnova.so: a sanitizer runtime cannot be loaded into a running Python.  GPU code
+    is not part of it.  Returns what the two programs printed; raises if one of them fails."""
+    os.makedirs(OBJ, exist_ok=True)
+    oracle_dir = os.path.join(HERE, "..", "oracle")
+    host = os.path.join(OBJ, "host_selftest_sanitized")
+    orac = os.path.join(OBJ, "conv_oracle_selftest_sanitized")
+    subprocess.check_call(["g++", "-std=c++17", "-pthread"] + SANITIZE + ["-o", host] +
+                          [os.path.join(SRC, f) for f in ("host_selftest.cpp", "transforms.cpp", "discovery.cpp")])
+    subprocess.check_call(["gcc", "-std=c11", "-ffp-contract=off", "-fopenmp"] + SANITIZE +
+                          ["-o", orac, os.path.join(oracle_dir, "conv_oracle_selftest.c"), "-lm"])
+    out = []
+    for prog in (host, orac):
+        res = subprocess.run([prog], capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError(f"{os.path.basename(prog)} failed ({res.returncode}):\n{res.stdout}\n{res.stderr}")
+        out.append(res.stdout.strip())
+    return out
+
+
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv))
+    if "--sanitize" in sys.argv:
+        print("\n".join(sanitize_selftest()))
+    else:
+        print(build(force="--force" in sys.argv))

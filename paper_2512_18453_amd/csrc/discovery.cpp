@@ -153,7 +153,7 @@ extern "C" int nova_snap_to_rational(double x, int d_max, nova_rational *out)
     long long best_a = 0, best_d = 1;
     for (long long d = 1; d <= d_max; ++d)
         for (long long a = -bound * d; a <= bound * d; ++a) {
-            i128 num = (i128)M * d - ((i128)a << s);
+            i128 num = (i128)M * d - (i128)a * ((i128)1 << s);      // (a product: shifting a negative value left is undefined before C++20)
             if (num < 0) num = -num;
             // num / d < best_num / best_d  <=>  num * best_d < best_num * d
             if (!have || num * best_d < best_num * d) { have = true; best_num = num; best_a = a; best_d = d; }
@@ -350,7 +350,8 @@ extern "C" int nova_snap_points(int m, int r, const double *x, int d_max, nova_r
             if (sh < 0 || sh > 100) return NOVA_EUNSUPPORTED;    // |x| beyond 2^53 or below 2^-47: not a point anyone means
             auto dist_less = [&](const Cand &u, const Cand &v) {
                 // |M 2^-sh - u.a/u.b| < |.. v ..|  <=>  |M u.b - u.a 2^sh| v.b < |M v.b - v.a 2^sh| u.b
-                i128 du = (i128)M * u.b - ((i128)u.a << sh), dv = (i128)M * v.b - ((i128)v.a << sh);
+                const i128 unit = (i128)1 << sh;
+                i128 du = (i128)M * u.b - (i128)u.a * unit, dv = (i128)M * v.b - (i128)v.a * unit;
                 if (du < 0) du = -du;
                 if (dv < 0) dv = -dv;
                 const i128 l = du * v.b, rr = dv * u.b;
