@@ -104,17 +104,6 @@ def main():
     def step():
         nova.nova_winograd_conv2d(t, xd, U, K, y=y, flags=flags, workspace=ws)
 
-    # clock ramp: a GPU that has been idle runs its first ~10 ms about 7 % slower, whatever the work is.  20 ms of
-    # plain device copies (no step of the workload) before the warm-up steps; reported as config.preheat
-    heat_src = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
-    heat_dst = torch.empty_like(heat_src)
-    torch.cuda.synchronize()
-    heat_t0 = time.perf_counter()
-    while time.perf_counter() - heat_t0 < 0.020:
-        for _ in range(20):
-            heat_dst.copy_(heat_src)
-        torch.cuda.synchronize()
-    del heat_src, heat_dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -178,6 +167,24 @@ def main():
         stages["output_transform"] = dict(us=s_out * 1e6, bytes=M_b + y_b, gbs=(M_b + y_b) / s_out / 1e9)
     for st in stages.values():
         st["hbm_frac"] = st["gbs"] / HBM_PEAK_GBS
+    # context for the fractions above: what a plain device copy moving the same number of bytes (half read, half
+    # written) takes on this machine; the 8 TB/s peak stays the roofline's peak
+    if not args.headline_only:
+        most = max(st["bytes"] for st in stages.values()) // 2
+        c_src = torch.empty(most, dtype=torch.uint8, device=dev)
+        c_dst = torch.empty(most, dtype=torch.uint8, device=dev)
+        for st in stages.values():
+            half = st["bytes"] // 2
+            for _ in range(5):
+                c_dst[:half].copy_(c_src[:half])
+            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            c0.record()
+            for _ in range(20):
+                c_dst[:half].copy_(c_src[:half])
+            c1.record()
+            torch.cuda.synchronize()
+            st["copy_same_bytes_us"] = c0.elapsed_time(c1) / 20 * 1e3
+        del c_src, c_dst
     dominant = max(stages, key=lambda k: stages[k]["us"])
     dom = stages[dominant]
     traffic = measured_traffic(nova.nova_version(), args.workload, args.points, "f16" if m_es == 2 else "f32",
@@ -310,8 +317,7 @@ def main():
         "config": {"workload": f"{args.workload}: 3x3 conv N={N} C={C} K={K} H=W={H}, F({m},3), {args.points} points",
                    "points": args.points, "images_per_slab": int(slab_imgs), "slabs": int(n_slabs),
                    "products_dtype": "f16" if m_es == 2 else "f32",
-                   "kernels": ["stages", "few_channels", "fused_output"][path],
-                   "preheat": "20 ms of plain device copies before the warm-up steps (clock ramp after idle)"},
+                   "kernels": ["stages", "few_channels", "fused_output"][path]},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "stages": {k: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()}
