@@ -337,8 +337,8 @@ int nova_winograd_conv2d_int8(const nova_transforms *t, const void *x, const voi
  * nova_conv2d_path says which kernels nova_winograd_conv2d runs for a layer shape (whatever the batch):
  * NOVA_PATH_STAGES (input transform, contraction, output transform), NOVA_PATH_FEW_CHANNELS (at most 4
  * input channels: compact V, the products formed inside the output transform) or NOVA_PATH_FUSED_OUTPUT
- * (input transform, then the kernel above: taken where it is supported and measured faster -- every
- * F(8,3) shape, F(6,3) where 16 tiles span the image width).  Negative: an error code.  Host only.
+ * (input transform, then the kernel above: taken wherever it is supported).  Negative: an error code.
+ * Host only.
  */
 enum { NOVA_PATH_STAGES = 0, NOVA_PATH_FEW_CHANNELS = 1, NOVA_PATH_FUSED_OUTPUT = 2 };
 int nova_conv2d_path(const nova_transforms *t, int C, int H, int W, int K, int dtype, int flags);

@@ -4,8 +4,8 @@
 // M never exists in memory: Y = A^T [ sum_c U * V ] A is formed per (tile, channel) pair from
 // matrix-unit results that stay in registers (Sec. 2.1 steps 3 and 4).
 //
-// A workgroup of 8 waves takes 16 neighbouring tiles (one group of a tile row, or a few tile rows of
-// a narrow image) and 64 output channels; a wave takes 8 of those channels.  Per Winograd-domain
+// A workgroup of 8 waves takes a block of up to 16 tiles (trb tile rows x twc tile columns, the shape that
+// wastes the fewest of the 16 slots over the image) and 64 output channels; a wave takes 8 of those channels.  Per Winograd-domain
 // position xi a wave forms a 16 x 16 block (v_mfma_f32_16x16x32_f16, binary32 accumulation over the
 // input channels) of which only 8 rows are used: the matrix unit leaves each lane 4 results (rows
 // 4 * (lane / 16) + 0..3 of column lane % 16), and the transform state of a (tile, channel) pair is
@@ -102,8 +102,8 @@ fused_contract_output_kernel(const f16 *__restrict__ U, const f16 *__restrict__ 
     const int tg = bid % sh.groups; bid /= sh.groups;
     const int tr = (bid % row_groups) * sh.trb; bid /= row_groups;
     const int img = bid;
-    const int tc0 = sh.trb > 1 ? 0 : tg * sh.twb;
-    // the group's tiles are neighbours in t (a group of several tile rows spans the image width)
+    const int tc0 = tg * sh.twc;
+    // tile j of the group: row j / twc, column j % twc of a block of trb x twc tiles
     const long long t0 = ((long long)img * tiles_h + tr) * tiles_w + tc0;
     const int k0 = kg * kFusedChannels, kw0 = k0 + wave * kFusedWaveChannels;
 
@@ -114,7 +114,7 @@ fused_contract_output_kernel(const f16 *__restrict__ U, const f16 *__restrict__ 
     // U: one load = one position (8 channels each of the two channel blocks): lane l -> block l / 32,
     //    row (l / 4) % 8, place l % 4.
     const int v_row_l = lane >> 2, v_piece_l = (lane & 3) ^ ((v_row_l >> 1) & 3);
-    long long v_t = t0 + v_row_l;
+    long long v_t = t0 + (long long)(v_row_l / sh.twc) * tiles_w + v_row_l % sh.twc;
     if (v_t > Ttot - 1) v_t = Ttot - 1;               // rows past the end: reread the last tile (never used)
     const unsigned v_lane_off = (unsigned)(((unsigned)v_t * kChanBlock + (unsigned)v_piece_l * 8u) * sizeof(f16));
     const size_t v_cb_stride = (size_t)Ttot * kChanBlock;          // elements per channel block of a position
@@ -303,8 +303,7 @@ fused_contract_output_kernel(const f16 *__restrict__ U, const f16 *__restrict__ 
     // ---- the results leave through LDS: all 64 channels at once if the block fits, else 32 at a time
     f16 *stage = reinterpret_cast<f16 *>(lds_raw);
     const int tile = lane & 15;
-    int jr = 0, jc = tile;
-    if (sh.trb > 1) { jr = tile / tiles_w; jc = tile - jr * tiles_w; }
+    const int jr = tile / sh.twc, jc = tile - jr * sh.twc;
     const bool active = tile < sh.twb && tc0 + jc < tiles_w && tr + jr < tiles_h;
     const float floor_at = relu ? 0.0f : -__builtin_inff();          // val < floor ? floor : val keeps a NaN
     constexpr int KB = kFusedChannels / kChanBlock;
@@ -346,15 +345,24 @@ static int launch_fused_shape(const nova_transforms *t, const void *U, const voi
     for (int p = 0; p < M; ++p) fold.c[p] = p == 0 ? coef.zero : 0.0f;
     for (int d = 1; d < N / 2; ++d)
         for (int p = 0; p < M; ++p) fold.c[d * M + p] = coef.pw[(d - 1) * M + p];
+    // The 16 tile slots of a workgroup are a block of trb x twc tiles.  Chosen: the block shape with the lowest
+    // estimated cost per tile of the image -- slots launched (ragged last blocks and twc * trb < 16 waste some)
+    // times a factor 1 + 1.2 / twc for narrow blocks (short runs of V and of y; fitted to timings: 4 x 4 blocks
+    // cost 1.14-1.22 times what full rows of 10-14 tiles cost per slot) -- among those whose output block leaves
+    // in 16-byte stores (its width a whole number of pieces, or one block spanning the image width).
+    const bool aligned = ((uintptr_t)y % 16) == 0;
+    int twb = 1, trb = 1;
+    double best = -1.0;
+    for (int tc = 1; tc <= kFusedTiles && tc <= g.tiles_w; ++tc)
+        for (int tr = 1; tr * tc <= kFusedTiles && tr <= g.tiles_h; ++tr) {
+            const int across = ceil_div(g.tiles_w, tc), down = ceil_div(g.tiles_h, tr);
+            const bool fast = aligned && (across == 1 || (g.W % PE == 0 && (tc * M) % PE == 0));
+            const double used = (double)g.tiles_w * g.tiles_h / ((double)across * down * kFusedTiles);
+            const double merit = used / (1.0 + 1.2 / tc) * (fast ? 1.0 : 0.5);
+            if (merit > best * (1.0 + 1e-9)) { best = merit; twb = tc; trb = tr; }
+        }
     OutShape sh;
-    sh.groups = ceil_div(g.tiles_w, kFusedTiles);
-    const int twb = ceil_div(g.tiles_w, sh.groups);
-    int trb = 1;
-    if (sh.groups == 1) {
-        trb = kFusedTiles / twb;
-        if (trb > g.tiles_h) trb = g.tiles_h;
-        trb = ceil_div(g.tiles_h, ceil_div(g.tiles_h, trb));     // same number of groups, evenly sized
-    }
+    sh.groups = ceil_div(g.tiles_w, twb);
     const size_t stage_bytes = out_shape<N, R, f16>(twb, trb, sh);
     const size_t loop_bytes = (size_t)2 * N * CB * kFusedTiles * 64 + (size_t)kFusedWaves * N * CB * kFusedWaveChannels * 64;
     const int one_pass = 2 * stage_bytes <= 160 * 1024 ? 1 : 0;       // both blocks of 32 channels staged together
@@ -363,7 +371,6 @@ static int launch_fused_shape(const nova_transforms *t, const void *U, const voi
     if (lds_bytes > 160 * 1024 || sh.twb > kFusedTiles) return (int)hipErrorInvalidValue;
     // 32-bit byte offsets inside one position of V
     if ((size_t)CB * g.T * kChanBlock * sizeof(f16) >= ((size_t)1 << 32)) return (int)hipErrorInvalidValue;
-    const bool aligned = ((uintptr_t)y % 16) == 0;
     const bool vec = g.W % PE == 0 && aligned && (sh.groups == 1 || (twb * M) % PE == 0);
     const bool flat = !vec && aligned && sh.groups == 1 && g.W >= 2 && sh.rows * g.W + 2 * (PE - 1) >= 2 * PE &&
                       (long long)sh.rows * g.W < (1 << 15);
@@ -399,12 +406,11 @@ bool fused_contract_output_applies(const nova_transforms *t, const Geometry &g, 
            g.C == kFusedCB * kChanBlock && g.K % kFusedChannels == 0 && g.T <= 0x7fffffffLL;
 }
 
-// ... and those for which it is the faster way (measured against contraction + output transform on one
-// MI355X): every F(8,3) shape it takes; F(6,3) -- more tiles per image, fewer outputs per tile -- only where one
-// group of 16 tiles spans a tile row (images up to 96 wide), elsewhere the two are level.
+// ... and those for which nova_winograd_conv2d takes it: all of them (measured against contraction + output
+// transform on one MI355X, F(8,3) and F(6,3), 224 x 224 down to 13 x 13: faster on every shape it takes).
 bool fused_contract_output_preferred(const nova_transforms *t, const Geometry &g, int dtype, int flags)
 {
-    return fused_contract_output_applies(t, g, dtype, flags) && (t->n == 10 || g.tiles_w <= kFusedTiles);
+    return fused_contract_output_applies(t, g, dtype, flags);
 }
 
 int launch_fused_contract_output(const nova_transforms *t, const void *U, const void *V, void *y, const Geometry &g,

@@ -60,7 +60,8 @@ __device__ __forceinline__ void output_transform_1d(const float (&v)[N], float (
 
 struct OutShape {
     int twb;          // tiles per group (all tile rows of the group together)
-    int trb;          // tile rows per group; > 1 only if a group spans the image width
+    int twc;          // tile columns per group
+    int trb;          // tile rows per group
     int rows;         // output rows per group = trb * m
     int groups;       // tile groups per tile row
     int cols_pitch;   // LDS elements per output row of the group
@@ -91,12 +92,50 @@ __device__ __forceinline__ void store_output_block(const T *lds, T *__restrict__
     typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
     const int w0 = tc0 * M;
-    int cols = (sh.trb > 1 ? tiles_w : sh.twb) * M;
+    int cols = sh.twc * M;
     if (w0 + cols > W) cols = W - w0;
     if (sh.pool) {
         // 2 x 2 max-pool on the way out: rows, columns, H, W, tr*M and w0 are all even, so no window
         // straddles two groups.  One output element per thread and round, lanes along the pooled row.
         const int Hp = H / 2, Wp = W / 2, pcols = cols / 2, prows = sh.rows / 2;
+        if constexpr (STG == kStoreVec && sizeof(T) == 2) {
+            // W, w0 and cols are multiples of a 16-byte piece of y and y is 16-byte aligned.  If they are multiples
+            // of two pieces, the pooled rows leave in 16-byte pieces too: a thread takes 2 rows x 16 columns.
+            if (W % (2 * PE) == 0 && w0 % (2 * PE) == 0 && cols % (2 * PE) == 0) {
+                const int pieces = pcols / PE;
+                const unsigned magic = (unsigned)((((unsigned long long)1 << 32) + pieces - 1) / pieces);
+                const int slots = kChanBlock * prows * pieces;
+                for (int s = threadIdx.x; s < slots; s += (int)blockDim.x) {
+                    const int line = pieces > 1 ? (int)__umulhi((unsigned)s, magic) : s;
+                    const int q = s - line * pieces;
+                    const int kk = prows > 1 ? (int)__umulhi((unsigned)line, sh.half_rows_magic) : line;
+                    const int pp = line - kk * prows;
+                    const int k = kb * kChanBlock + kk, hp = (tr * M) / 2 + pp;
+                    if (k >= K || hp >= Hp) continue;
+                    const T *top = lds + kk * sh.k_pitch + 2 * pp * sh.cols_pitch + 2 * q * PE;     // 8-byte aligned
+                    const T *bottom = top + sh.cols_pitch;
+                    T a[2 * PE], b[2 * PE], out[PE];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        reinterpret_cast<u32x2 *>(a)[e] = reinterpret_cast<const u32x2 *>(top)[e];
+                        reinterpret_cast<u32x2 *>(b)[e] = reinterpret_cast<const u32x2 *>(bottom)[e];
+                    }
+#pragma unroll
+                    for (int e = 0; e < PE; ++e) {
+                        const float v0 = (float)a[2 * e], v1 = (float)a[2 * e + 1], v2 = (float)b[2 * e], v3 = (float)b[2 * e + 1];
+                        float best = v0;                                  // a NaN in the window wins
+                        best = (v1 > best || v1 != v1) ? v1 : best;
+                        best = (v2 > best || v2 != v2) ? v2 : best;
+                        best = (v3 > best || v3 != v3) ? v3 : best;
+                        out[e] = (T)best;                                 // one of the four values: exact
+                    }
+                    u32x4 piece;
+                    __builtin_memcpy(&piece, out, 16);
+                    __builtin_nontemporal_store(piece, reinterpret_cast<u32x4 *>(y + (((size_t)img * K + k) * Hp + hp) * Wp + w0 / 2 + q * PE));
+                }
+                return;
+            }
+        }
         const unsigned pc_magic = (unsigned)((((unsigned long long)1 << 32) + pcols - 1) / pcols);
         const int slots = kChanBlock * prows * pcols;
         for (int s = threadIdx.x; s < slots; s += (int)blockDim.x) {
@@ -203,6 +242,7 @@ static size_t out_shape(int twb, int trb, OutShape &sh)
 {
     constexpr int M = N - R + 1;
     sh.twb = twb * trb;
+    sh.twc = twb;
     sh.trb = trb;
     sh.rows = trb * M;
     sh.rows_magic = (unsigned)((((unsigned long long)1 << 32) + sh.rows - 1) / sh.rows);
