@@ -775,6 +775,9 @@ FUSED_CASES = [
     (6, 2, 64, 128, 56, 56),
     (6, 3, 64, 64, 45, 100),
     (6, 2, 64, 64, 13, 13),
+    (6, 1, 64, 64, 112, 112),       # 19 x 19 tiles in 4 x 4 blocks
+    (6, 1, 64, 64, 224, 224),       # 38 x 38 tiles in 2 x 8 blocks
+    (8, 2, 64, 64, 100, 36),        # widths that are no whole number of 16-byte pieces
 ]
 
 
@@ -912,6 +915,8 @@ POISON_CASES = [
     (4, 3, 4, 20, 13, 9, "f32"),
     (4, 2, 33, 50, 19, 22, "f32"),
     (8, 7, 128, 64, 28, 28, "f16"),          # streaming contraction with a ragged last stage
+    (8, 3, 64, 64, 17, 23, "f16"),           # contraction + output transform in one kernel, ragged tile block
+    (6, 2, 64, 128, 112, 100, "f16"),        # ... in 4 x 4 tile blocks with ragged last blocks both ways
 ]
 
 
