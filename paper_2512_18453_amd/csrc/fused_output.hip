@@ -4,9 +4,9 @@
 // M never exists in memory: Y = A^T [ sum_c U * V ] A is formed per (tile, channel) pair from
 // matrix-unit results that stay in registers (Sec. 2.1 steps 3 and 4).
 //
-// A workgroup of 8 waves takes a block of up to 16 tiles (trb tile rows x twc tile columns, the shape that
-// wastes the fewest of the 16 slots over the image) and 64 output channels; a wave takes 8 of those channels.  Per Winograd-domain
-// position xi a wave forms a 16 x 16 block (v_mfma_f32_16x16x32_f16, binary32 accumulation over the
+// A workgroup of 8 waves takes a block of up to 16 tiles (trb tile rows x twc tile columns, the shape
+// that wastes the fewest of the 16 slots over the image) and 64 output channels; a wave takes 8 of those
+// channels.  Per Winograd-domain position xi a wave forms a 16 x 16 block (v_mfma_f32_16x16x32_f16, binary32 accumulation over the
 // input channels) of which only 8 rows are used: the matrix unit leaves each lane 4 results (rows
 // 4 * (lane / 16) + 0..3 of column lane % 16), and the transform state of a (tile, channel) pair is
 // m*m + m values, so a lane can carry two pairs, not four -- rows 2 and 3 of every group of four repeat
@@ -18,9 +18,10 @@
 // outputs, Y[p][q] += A[i][p] w[q]; the rows of +a and -a enter together through their sum and
 // difference, which halves the multiplications (as in the separate output transform).  The row loop
 // is unrolled by two -- rows 2d and 2d + 1 -- so that buffers, ring places and the fold are the same
-// code for every d: the fold after row 2d takes the pair (2d - 1, 2d) with the coefficient row fold[d]
-// (for d = 0 the carried row is zero and fold[0] = (A[0][0], 0, ...): the point 0), row n - 1 (the
-// point at infinity) is added after the loop.
+// code for every d: the pair of rows (2d - 1, 2d) is folded with the coefficient row fold[d] (for d = 0
+// the carried row is zero and fold[0] = (A[0][0], 0, ...): the point 0), row n - 1 (the point at
+// infinity) is added after the loop.  The vector work on a row runs a row late, cut into slices that
+// sit between the matrix instructions of the next row, whose fragments are read two positions ahead.
 //
 // Operands.  V[xi] of the 16 tiles (64 channels: 2 KiB) is shared by the 8 waves: two LDS buffers of
 // one row of positions each, filled by direct global->LDS loads a row ahead, one barrier per row.
@@ -34,8 +35,9 @@
 // pattern that a 128-bit fragment read of rows lane % 16 takes fastest (timed: 2.9 clocks per wave-wide
 // read against 4.5 without it or with (row / 4) % 4, which is the right one for rows lane % 32); the
 // loads fix each lane's place in LDS, so a lane fetches the piece that belongs there.
-// At the end the m x m results of all pairs go through LDS as [32 channels][rows][columns] blocks (two
-// passes of 32 channels) and leave as in the separate output transform, with its ReLU / max-pool options.
+// At the end the m x m results of all pairs go through LDS as [32 channels][rows][columns] blocks (both
+// blocks at once if they fit, else two passes) and leave as in the separate output transform, with its
+// ReLU / max-pool options.
 #include "output_common.hpp"
 
 namespace nova {
