@@ -330,7 +330,7 @@ int nova_winograd_conv2d_int8(const nova_transforms *t, const void *x, const voi
  * Steps 3 and 4 (Sec. 2.1) in one kernel: y = A^T [ sum_c U * V ] A per tile and output channel, the
  * products kept in registers and never written as M.  For layers with 64 input channels, where M is
  * most of the memory traffic: NOVA_F16 storage, points in the order 0, +a, -a, .., F(6,3) or F(8,3),
- * C = 64, K a multiple of 64, without NOVA_FLAG_M_F16; other requests: NOVA_EUNSUPPORTED.
+ * C = 64, K a multiple of 32, without NOVA_FLAG_M_F16; other requests: NOVA_EUNSUPPORTED.
  * U, V as for nova_contract; y, flags (ReLU, max-pool) as for nova_output_transform.  The result differs
  * from nova_contract + nova_output_transform by the order of the binary32 sums only.
  *

@@ -4,10 +4,13 @@
 // M never exists in memory: Y = A^T [ sum_c U * V ] A is formed per (tile, channel) pair from
 // matrix-unit results that stay in registers (Sec. 2.1 steps 3 and 4).
 //
-// A workgroup of 8 waves takes a block of up to 16 tiles (trb tile rows x twc tile columns, the shape
-// that wastes the fewest of the 16 slots over the image) and 64 output channels; a wave takes 8 of those
-// channels.  Per Winograd-domain position xi a wave forms a 16 x 16 block (v_mfma_f32_16x16x32_f16, binary32 accumulation over the
-// input channels) of which only 8 rows are used: the matrix unit leaves each lane 4 results (rows
+// A workgroup of 4 waves takes a block of up to 16 tiles (trb tile rows x twc tile columns, the shape
+// that wastes the fewest of the 16 slots over the image) and 32 output channels; a wave takes 8 of those
+// channels.  Two workgroups share a compute unit (80 KB of LDS and at most 256 registers each), so that the
+// head and the tail of one -- waiting for the first operands, converting, staging and storing the results,
+// 40 % of its life -- overlap the other's main loop (8 waves as one workgroup per unit: 3-19 % slower).
+// Per Winograd-domain position xi a wave forms a 16 x 16 block (v_mfma_f32_16x16x32_f16, binary32
+// accumulation over the input channels) of which only 8 rows are used: the matrix unit leaves each lane 4 results (rows
 // 4 * (lane / 16) + 0..3 of column lane % 16), and the transform state of a (tile, channel) pair is
 // m*m + m values, so a lane can carry two pairs, not four -- rows 2 and 3 of every group of four repeat
 // rows 0 and 1 and their results are dropped.  The matrix unit has the time: the kernel is bound by
@@ -23,21 +26,20 @@
 // infinity) is added after the loop.  The vector work on a row runs a row late, cut into slices that
 // sit between the matrix instructions of the next row, whose fragments are read two positions ahead.
 //
-// Operands.  V[xi] of the 16 tiles (64 channels: 2 KiB) is shared by the 8 waves: two LDS buffers of
+// Operands.  V[xi] of the 16 tiles (64 channels: 2 KiB) is shared by the 4 waves: two LDS buffers of
 // one row of positions each, filled by direct global->LDS loads a row ahead, one barrier per row.
 // U[xi] of a wave's 8 channels (1 KiB) is private to the wave: a ring of one row of positions in LDS,
 // refilled for the next row, half a row at a time, right after the half has been read, and waited for
 // by the wave alone (vector-memory operations of a wave complete in the order issued, so "at most
 // the loads issued after these are outstanding" is a count).  Every LDS address in the loop is a
 // per-lane base plus an immediate.  U comes from L2 (the whole of U is under a MB at these channel
-// counts), V from memory, once per group of 64 output channels.
+// counts), V from memory or L2, once per group of 32 output channels (neighbouring workgroups).
 // LDS rows of 64 bytes (32 channels) are XOR-swizzled by 16-byte piece -- piece ^ ((row / 2) % 4), the
 // pattern that a 128-bit fragment read of rows lane % 16 takes fastest (timed: 2.9 clocks per wave-wide
 // read against 4.5 without it or with (row / 4) % 4, which is the right one for rows lane % 32); the
 // loads fix each lane's place in LDS, so a lane fetches the piece that belongs there.
-// At the end the m x m results of all pairs go through LDS as [32 channels][rows][columns] blocks (both
-// blocks at once if they fit, else two passes) and leave as in the separate output transform, with its
-// ReLU / max-pool options.
+// At the end the m x m results of all pairs go through LDS as a [32 channels][rows][columns] block and
+// leave as in the separate output transform, with its ReLU / max-pool options.
 #include "output_common.hpp"
 
 namespace nova {
@@ -46,7 +48,7 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 
 constexpr int kFusedTiles = 16;        // tiles per workgroup: the columns of the matrix instruction
-constexpr int kFusedWaves = 8;
+constexpr int kFusedWaves = 4;         // 32 output channels per workgroup; two workgroups share a compute unit
 constexpr int kFusedWaveChannels = 8;  // output channels per wave
 constexpr int kFusedChannels = kFusedWaves * kFusedWaveChannels;
 constexpr int kFusedCB = 2;            // blocks of 32 input channels
@@ -367,8 +369,9 @@ static int launch_fused_shape(const nova_transforms *t, const void *U, const voi
     sh.groups = ceil_div(g.tiles_w, twb);
     const size_t stage_bytes = out_shape<N, R, f16>(twb, trb, sh);
     const size_t loop_bytes = (size_t)2 * N * CB * kFusedTiles * 64 + (size_t)kFusedWaves * N * CB * kFusedWaveChannels * 64;
-    const int one_pass = 2 * stage_bytes <= 160 * 1024 ? 1 : 0;       // both blocks of 32 channels staged together
-    const size_t out_bytes = one_pass ? 2 * stage_bytes : stage_bytes;
+    constexpr int KB = kFusedChannels / kChanBlock;
+    const int one_pass = KB * stage_bytes <= 160 * 1024 ? 1 : 0;      // all blocks of 32 channels staged together
+    const size_t out_bytes = one_pass ? KB * stage_bytes : stage_bytes;
     const size_t lds_bytes = out_bytes > loop_bytes ? out_bytes : loop_bytes;
     if (lds_bytes > 160 * 1024 || sh.twb > kFusedTiles) return (int)hipErrorInvalidValue;
     // 32-bit byte offsets inside one position of V
@@ -401,7 +404,7 @@ static int launch_fused_shape(const nova_transforms *t, const void *U, const voi
 }
 
 // Shapes the fused kernel takes: binary16 storage, products not rounded to binary16, points in the paired
-// order, F(6,3) or F(8,3), C = 64, K a multiple of 64.
+// order, F(6,3) or F(8,3), C = 64, K a multiple of 32.
 bool fused_contract_output_applies(const nova_transforms *t, const Geometry &g, int dtype, int flags)
 {
     return dtype == NOVA_F16 && !(flags & NOVA_FLAG_M_F16) && t->symmetric && t->r == 3 && (t->n == 8 || t->n == 10) &&
