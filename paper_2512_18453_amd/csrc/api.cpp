@@ -360,4 +360,4 @@ extern "C" const char *nova_strerror(int code)
 }
 
 extern "C" int nova_last_hip_error(void) { return g_last_hip_error; }
-extern "C" const char *nova_version(void) { return "libnova 0.4 (gfx950)"; }
+extern "C" const char *nova_version(void) { return "libnova 0.5 (gfx950)"; }
