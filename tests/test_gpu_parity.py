@@ -778,6 +778,8 @@ FUSED_CASES = [
     (6, 1, 64, 64, 112, 112),       # 19 x 19 tiles in 4 x 4 blocks
     (6, 1, 64, 64, 224, 224),       # 38 x 38 tiles in 2 x 8 blocks
     (8, 2, 64, 64, 100, 36),        # widths that are no whole number of 16-byte pieces
+    (8, 1, 64, 32, 1, 1),           # one pixel, one group of 32 output channels
+    (6, 3, 64, 32, 5, 64),          # a single tile row, images smaller than a tile high
 ]
 
 
